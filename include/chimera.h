@@ -1,0 +1,232 @@
+/*
+ * chimera.h - C ABI of one Chimera pipeline worker on one MI355X (gfx950).
+ *
+ * Chimera (Li & Hoefler, SC'21) runs two pipelines in opposite directions
+ * through the same D workers.  Worker i owns stage i of the "down" pipeline
+ * and stage D-1-i of the "up" pipeline (section 3.1).  Within one training
+ * iteration every worker runs N micro-batches, N/2 through each of its two
+ * stages, in the order given by the merged 1F1B schedule; the weight
+ * gradients of a stage are summed over its micro-batches with one weight
+ * version (section 2, "Convergence friendliness").  This library is that
+ * worker: a schedule generator (CPU), a stage (L pre-LayerNorm Transformer
+ * blocks, forward and backward, HIP kernels) and the replay of the worker's
+ * op list on a HIP stream.  Activations arriving from the previous stage and
+ * gradients arriving from the next stage are buffers the caller provides.
+ *
+ * General rules
+ *  - Every function returns CHIMERA_OK (0) or a negative error code; none
+ *    aborts or throws.  chimera_last_error() gives the text of the last
+ *    failure on the calling thread.
+ *  - Pointers named d_* are DEVICE pointers, h_* HOST pointers.  The library
+ *    never allocates or frees device memory: the caller owns every device
+ *    buffer and must keep it alive while the stage uses it.
+ *  - A stage enqueues all its work on the HIP stream given to
+ *    chimera_stage_bind (a hipStream_t passed as void*; NULL = default
+ *    stream).  Calls return once the work is enqueued unless stated otherwise.
+ *  - A stage and the worker binding are not thread-safe.
+ *
+ * Tensor layouts.  M = microbatch*seq tokens, H = hidden, d = H/heads.
+ * Activations are row-major [M, H], token index = b*seq + s.  Element type is
+ * the stage dtype (float or bf16); parameter gradients are always float.
+ * Parameters live in ONE flat buffer, block after block, inside a block in
+ * this order (all row-major, linear maps stored [in, out], y = x W + b):
+ *     ln1_g[H] ln1_b[H] w_qkv[H,3H] b_qkv[3H] w_o[H,H] b_o[H]
+ *     ln2_g[H] ln2_b[H] w_fc1[H,4H] b_fc1[4H] w_fc2[4H,H] b_fc2[H]
+ * w_qkv's columns are [Q | K | V]; head j owns columns j*d..(j+1)*d-1 of each.
+ * The gradient buffer has the same order and element counts.
+ * One block computes (the paper leaves the block unspecified; this is the
+ * GPT-2 style reading):
+ *     x1 = x + (Attn(LN1(x) w_qkv + b_qkv)) w_o + b_o
+ *     y  = x1 + GeLU(LN2(x1) w_fc1 + b_fc1) w_fc2 + b_fc2
+ * LayerNorm: biased variance, eps 1e-5.  Attention: softmax(q k^T / sqrt(d))
+ * with an optional causal mask (key <= query).
+ */
+#ifndef CHIMERA_H
+#define CHIMERA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CHIMERA_OK = 0,
+    CHIMERA_EINVAL = -1,  /* bad argument                                   */
+    CHIMERA_ENOMEM = -2,  /* a caller-provided buffer or capacity too small */
+    CHIMERA_ESTATE = -3,  /* call out of order (see each function)          */
+    CHIMERA_EDEVICE = -4  /* a HIP call failed                              */
+};
+
+enum { CHIMERA_F32 = 0, CHIMERA_BF16 = 1 };
+
+/* schedule algorithms */
+enum { CHIMERA_DIRECT = 0, CHIMERA_GPIPE = 1, CHIMERA_1F1B = 2 };
+
+/* stage options (chimera_stage_set_option) */
+enum {
+    CHIMERA_OPT_CAUSAL = 0,  /* 1 (default) = causal mask, 0 = bidirectional        */
+    CHIMERA_OPT_GELU = 1,    /* 0 (default) = tanh form, 1 = exact erf form         */
+    CHIMERA_OPT_KERNELS = 2  /* 0 (default) = matrix-core kernels where the shape   */
+                             /* allows, 1 = plain reference kernels everywhere      */
+};
+
+typedef struct chimera_stage chimera_stage;
+
+/* Text of the last error on this thread; static storage, never NULL. */
+const char* chimera_last_error(void);
+
+/* ------------------------------------------------------------------ schedule
+ * Section 3.1 (bidirectional 1F1B merge), section 3.5 (direct concatenation
+ * of K = N/D basic units) and, as baselines, GPipe and 1F1B-with-flush
+ * (section 2, "Bubbles in the pipeline").  Pure CPU; usable without a GPU.
+ */
+typedef struct {
+    int32_t kind;   /* 0 = forward, 1 = backward                               */
+    int32_t pipe;   /* 0 = down pipeline, 1 = up pipeline (baselines: always 0) */
+    int32_t mb;     /* global micro-batch id, 0 .. N-1                          */
+    int32_t stage;  /* pipeline stage the op belongs to                         */
+    int32_t slot;   /* activation-stash slot of that stage used by this         */
+                    /* micro-batch (lowest free slot at its forward)            */
+    int32_t start;  /* start time when all workers replay as soon as possible   */
+                    /* with forward cost = backward cost = 1                    */
+    int32_t last_of_stage; /* 1 on the backward that completes this stage's     */
+                    /* weight gradients for the iteration (section 3.2)         */
+} chimera_op;
+
+/* Op list of worker `rank` in execution order.  Writes min(count, cap) ops to
+ * h_out (may be NULL if cap == 0) and the full count (2N) to *h_count.
+ * EINVAL: unknown algo; D < 1; N < 1; rank outside [0, D); for CHIMERA_DIRECT
+ * also D odd or N not a multiple of D.  ENOMEM: cap < count (list truncated). */
+int chimera_schedule(int algo, int D, int N, int rank,
+                     chimera_op* h_out, size_t cap, size_t* h_count);
+
+/* Replays all D workers as soon as possible under the data dependencies with
+ * integer costs (cost_f, cost_b >= 1).  Outputs (each may be NULL):
+ * *h_makespan; h_bubbles[D] = makespan - busy time per worker;
+ * h_stash_peak[D] = most micro-batches in flight per worker;
+ * h_critical[2] = forwards and backwards on the critical path (section 3.4). */
+int chimera_schedule_stats(int algo, int D, int N, int cost_f, int cost_b,
+                           int64_t* h_makespan, int64_t* h_bubbles,
+                           int32_t* h_stash_peak, int32_t* h_critical);
+
+/* --------------------------------------------------------------------- stage
+ * A stage = `layers` Transformer blocks at fixed shape (the paper's F_t / B_t
+ * black box, section 3.4).  Returns NULL on error (EINVAL: non-positive size,
+ * hidden % heads != 0, hidden % 8 != 0, unknown dtype). */
+chimera_stage* chimera_stage_create(int layers, int hidden, int heads, int seq,
+                                    int microbatch, int dtype);
+/* Only before chimera_stage_bind; ESTATE afterwards. */
+int chimera_stage_set_option(chimera_stage* st, int key, int value);
+void chimera_stage_destroy(chimera_stage* st);
+
+/* Sizes in bytes of the buffers the caller must provide. */
+size_t chimera_stage_weight_bytes(const chimera_stage* st);
+size_t chimera_stage_grad_bytes(const chimera_stage* st);
+size_t chimera_stage_stash_slot_bytes(const chimera_stage* st);
+size_t chimera_stage_workspace_bytes(const chimera_stage* st);
+
+/* Hands the stage its device buffers (all 256-byte aligned): weights
+ * (weight_bytes, stage dtype), gradients (grad_bytes, float), the activation
+ * stash (stash_slots * stash_slot_bytes), scratch (workspace_bytes) and the
+ * stream.  The stash holds what the backward of an in-flight micro-batch needs
+ * (the paper's M_a per slot; Chimera needs between D/2+1 and D slots per
+ * worker over its two stages, Table 2).  Buffers are borrowed, not copied. */
+int chimera_stage_bind(chimera_stage* st, const void* d_weights, float* d_grads,
+                       void* d_stash, int stash_slots, void* d_workspace,
+                       void* hip_stream);
+
+/* Registers the buffers of micro-batch `mb` (any non-negative id): d_x_in
+ * [M,H] activation from the previous stage, d_y_out [M,H] activation for the
+ * next stage, d_dy_in [M,H] gradient from the next stage, d_dx_out [M,H]
+ * gradient for the previous stage.  d_x_in is read again by the backward, so
+ * it must stay unchanged until chimera_bwd(mb) has run. */
+int chimera_stage_set_io(chimera_stage* st, int mb, const void* d_x_in, void* d_y_out,
+                         const void* d_dy_in, void* d_dx_out);
+
+/* Forward of micro-batch mb: takes a free stash slot (or `slot` >= 0 via
+ * chimera_fwd_slot), writes d_y_out.  ESTATE: stage not bound, io of mb not
+ * set, mb already in flight, no free slot / slot taken. */
+int chimera_fwd(chimera_stage* st, int mb);
+int chimera_fwd_slot(chimera_stage* st, int mb, int slot);
+/* Backward of micro-batch mb: writes d_dx_out, ADDS this micro-batch's
+ * parameter gradients to d_grads (float accumulation in call order), frees
+ * the slot.  ESTATE: forward of mb not done. */
+int chimera_bwd(chimera_stage* st, int mb);
+
+int chimera_stage_in_flight(const chimera_stage* st);
+int chimera_stage_zero_grads(chimera_stage* st);                 /* enqueued   */
+/* Copies the gradient buffer to host memory and waits for the stream. */
+int chimera_stage_read_grads(chimera_stage* st, float* h_dst, size_t bytes);
+
+/* -------------------------------------------------------------------- worker
+ * Section 3.1: a worker = its down stage and its up stage.  Both must be bound
+ * and have the io of every micro-batch they will see registered:
+ * the down stage sees ids k*D + 0..D/2-1, the up stage ids k*D + D/2..D-1. */
+int chimera_worker_bind(chimera_stage* down_stage, chimera_stage* up_stage);
+/* Replays chimera_schedule(CHIMERA_DIRECT, D, N, rank) on the bound stages in
+ * list order, using each op's stash slot, and waits for the stream(s) once at
+ * the end.  ENOMEM if a stage was bound with fewer slots than the schedule
+ * needs.  Both stages must have no micro-batch in flight. */
+int chimera_run_worker(int rank, int D, int N);
+/* Same for any algorithm; for the one-pipeline baselines only the down stage
+ * is used and holds stage `rank`. */
+int chimera_run_worker_algo(int algo, int rank, int D, int N);
+/* on != 0: bracket every op of the next replays with HIP events (off by default). */
+int chimera_worker_set_timing(int on);
+/* Milliseconds the last chimera_run_worker* spent in forward ops and in
+ * backward ops (HIP events around every op), and the op counts. */
+int chimera_worker_last_timing(double* h_fwd_ms, double* h_bwd_ms, int* h_nf, int* h_nb);
+
+/* ---------------------------------------------------------- single operators
+ * The kernels a stage is made of, callable on raw device buffers so that each
+ * can be checked and profiled alone.  dtype as above; `impl` 0 = the kernel
+ * the stage would pick, 1 = plain reference kernel.  All enqueue on
+ * `hip_stream`.
+ *
+ * GEMM  C[m,n] = sum_k A(i,k) B(k,j) with epilogue.  a_kc != 0: A stored
+ * [m, k] (k contiguous, leading dimension lda); a_kc == 0: A stored [k, m].
+ * b_kc != 0: B stored [n, k] (k contiguous); b_kc == 0: B stored [k, n].
+ * epilogue: 0 C = acc (dtype); 1 C = acc + bias[n]; 2 C = acc + bias[n] and
+ * C2 = GeLU(C); 3 C = acc + bias[n] + R[m,n]; 4 C = acc * GeLU'(R[m,n]);
+ * 5 C (float, always) += acc.  C, C2, R have leading dimension n.
+ * EINVAL if k, n or a leading dimension is not a multiple of 8. */
+int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind,
+                    int m, int n, int k,
+                    const void* d_a, int lda, int a_kc,
+                    const void* d_b, int ldb, int b_kc,
+                    const void* d_bias, const void* d_r,
+                    void* d_c, void* d_c2, void* hip_stream);
+/* y = LN(x) gamma + beta; mean, rstd [rows] float are written for the backward. */
+int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x,
+                             const void* d_gamma, const void* d_beta, void* d_y,
+                             float* d_mean, float* d_rstd, void* hip_stream);
+/* dx = res + LN'(dy); dgamma, dbeta (float) += column sums.  d_scratch: float
+ * [layernorm_bwd_scratch_floats(rows, cols)]. */
+size_t chimera_op_layernorm_bwd_scratch_floats(int rows, int cols);
+int chimera_op_layernorm_bwd(int dtype, int rows, int cols, const void* d_dy,
+                             const void* d_x, const float* d_mean, const float* d_rstd,
+                             const void* d_gamma, const void* d_res, void* d_dx,
+                             float* d_dgamma, float* d_dbeta, float* d_scratch,
+                             void* hip_stream);
+/* out[cols] (float) += sum over rows of x[rows, cols]. */
+size_t chimera_op_colsum_scratch_floats(int rows, int cols);
+int chimera_op_colsum(int dtype, int rows, int cols, const void* d_x, float* d_out,
+                      float* d_scratch, void* hip_stream);
+/* ctx[M,H] = softmax(q k^T / sqrt(d) [+ causal mask]) v per (sequence, head),
+ * q, k, v read from qkv [M, 3H]; lse [batch, heads, seq] float = log-sum-exp
+ * of the scaled scores (kept for the backward). */
+int chimera_op_attention_fwd(int dtype, int impl, int batch, int seq, int heads, int head_dim,
+                             int causal, const void* d_qkv, void* d_ctx, float* d_lse,
+                             void* hip_stream);
+/* dqkv [M,3H] from dctx [M,H]; d_delta: float scratch [batch*heads*seq]. */
+int chimera_op_attention_bwd(int dtype, int impl, int batch, int seq, int heads, int head_dim,
+                             int causal, const void* d_qkv, const void* d_ctx,
+                             const float* d_lse, const void* d_dctx, void* d_dqkv,
+                             float* d_delta, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHIMERA_H */

@@ -1,0 +1,266 @@
+"""ctypes binding of libchimera.so: the same names as include/chimera.h,
+argument marshalling only.  Device memory and streams come from PyTorch-ROCm;
+every computation runs inside the library."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libchimera.so")
+
+OK, EINVAL, ENOMEM, ESTATE, EDEVICE = 0, -1, -2, -3, -4
+F32, BF16 = 0, 1
+DIRECT, GPIPE, ONE_F_ONE_B = 0, 1, 2
+OPT_CAUSAL, OPT_GELU, OPT_KERNELS = 0, 1, 2
+EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL, EPI_DGELU, EPI_ACCUM_F32 = range(6)
+
+
+class ChimeraError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("chimera error %d: %s" % (code, text))
+        self.code = code
+
+
+class chimera_op(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("pipe", C.c_int32), ("mb", C.c_int32), ("stage", C.c_int32),
+                ("slot", C.c_int32), ("start", C.c_int32), ("last_of_stage", C.c_int32)]
+
+    def astuple(self):
+        return (self.kind, self.pipe, self.mb, self.stage)
+
+
+_p, _i, _sz = C.c_void_p, C.c_int, C.c_size_t
+_SIGNATURES = {
+    "chimera_last_error": (C.c_char_p, []),
+    "chimera_schedule": (_i, [_i, _i, _i, _i, C.POINTER(chimera_op), _sz, C.POINTER(_sz)]),
+    "chimera_schedule_stats": (_i, [_i, _i, _i, _i, _i, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                    C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "chimera_stage_create": (_p, [_i] * 6),
+    "chimera_stage_set_option": (_i, [_p, _i, _i]),
+    "chimera_stage_destroy": (None, [_p]),
+    "chimera_stage_weight_bytes": (_sz, [_p]),
+    "chimera_stage_grad_bytes": (_sz, [_p]),
+    "chimera_stage_stash_slot_bytes": (_sz, [_p]),
+    "chimera_stage_workspace_bytes": (_sz, [_p]),
+    "chimera_stage_bind": (_i, [_p, _p, _p, _p, _i, _p, _p]),
+    "chimera_stage_set_io": (_i, [_p, _i, _p, _p, _p, _p]),
+    "chimera_fwd": (_i, [_p, _i]),
+    "chimera_fwd_slot": (_i, [_p, _i, _i]),
+    "chimera_bwd": (_i, [_p, _i]),
+    "chimera_stage_in_flight": (_i, [_p]),
+    "chimera_stage_zero_grads": (_i, [_p]),
+    "chimera_stage_read_grads": (_i, [_p, _p, _sz]),
+    "chimera_worker_bind": (_i, [_p, _p]),
+    "chimera_run_worker": (_i, [_i, _i, _i]),
+    "chimera_run_worker_algo": (_i, [_i, _i, _i, _i]),
+    "chimera_worker_set_timing": (_i, [_i]),
+    "chimera_worker_last_timing": (_i, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i), C.POINTER(_i)]),
+    "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p]),
+    "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
+    "chimera_op_layernorm_bwd_scratch_floats": (_sz, [_i, _i]),
+    "chimera_op_layernorm_bwd": (_i, [_i, _i, _i] + [_p] * 11),
+    "chimera_op_colsum_scratch_floats": (_sz, [_i, _i]),
+    "chimera_op_colsum": (_i, [_i, _i, _i, _p, _p, _p, _p]),
+    "chimera_op_attention_fwd": (_i, [_i] * 7 + [_p, _p, _p, _p]),
+    "chimera_op_attention_bwd": (_i, [_i] * 7 + [_p] * 7),
+}
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: run `python -m paper_2107_06925_amd.build` "
+                              "(there is no CPU fallback)" % LIB_PATH)
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def last_error():
+    return lib().chimera_last_error().decode()
+
+
+def check(code):
+    if code != OK:
+        raise ChimeraError(code, last_error())
+    return code
+
+
+# ------------------------------------------------------------------ schedule
+def chimera_schedule(algo, D, N, rank):
+    n = _sz(0)
+    cap = 2 * max(N, 1)
+    buf = (chimera_op * cap)()
+    check(lib().chimera_schedule(algo, D, N, rank, buf, cap, C.byref(n)))
+    return list(buf[:n.value])
+
+
+def chimera_schedule_stats(algo, D, N, cost_f=1, cost_b=1):
+    mk = C.c_int64(0)
+    bub = (C.c_int64 * max(D, 1))()
+    peak = (C.c_int32 * max(D, 1))()
+    crit = (C.c_int32 * 2)()
+    check(lib().chimera_schedule_stats(algo, D, N, cost_f, cost_b, C.byref(mk), bub, peak, crit))
+    return dict(makespan=mk.value, bubbles=list(bub), stash_peak=list(peak), critical=(crit[0], crit[1]))
+
+
+# --------------------------------------------------------------------- stage
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class Stage:
+    """Owns the device buffers (torch tensors) a chimera_stage borrows."""
+
+    def __init__(self, layers, hidden, heads, seq, microbatch, dtype, causal=True, gelu_erf=False,
+                 reference_kernels=False, stash_slots=1, stream=None, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.handle = lib().chimera_stage_create(layers, hidden, heads, seq, microbatch, dtype)
+        if not self.handle:
+            raise ChimeraError(EINVAL, last_error())
+        self.layers, self.hidden, self.heads, self.seq, self.microbatch, self.dtype = layers, hidden, heads, seq, microbatch, dtype
+        check(lib().chimera_stage_set_option(self.handle, OPT_CAUSAL, int(bool(causal))))
+        check(lib().chimera_stage_set_option(self.handle, OPT_GELU, int(bool(gelu_erf))))
+        check(lib().chimera_stage_set_option(self.handle, OPT_KERNELS, int(bool(reference_kernels))))
+        self.tdtype = torch.float32 if dtype == F32 else torch.bfloat16
+        esz = 4 if dtype == F32 else 2
+        L = lib()
+        dev = torch.device(device)
+        self.device = dev
+        self.weights = torch.empty(L.chimera_stage_weight_bytes(self.handle) // esz, dtype=self.tdtype, device=dev)
+        self.grads = torch.zeros(L.chimera_stage_grad_bytes(self.handle) // 4, dtype=torch.float32, device=dev)
+        self.slot_bytes = L.chimera_stage_stash_slot_bytes(self.handle)
+        self.stash = torch.empty(self.slot_bytes * stash_slots, dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(L.chimera_stage_workspace_bytes(self.handle), dtype=torch.uint8, device=dev)
+        self.stash_slots = stash_slots
+        self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
+        check(L.chimera_stage_bind(self.handle, _ptr(self.weights), _ptr(self.grads), _ptr(self.stash), stash_slots,
+                                   _ptr(self.workspace), C.c_void_p(self.stream.cuda_stream)))
+        self.io = {}
+
+    def set_weights(self, flat_f32):
+        """flat_f32: numpy float32 vector in the flat parameter order."""
+        t = self.torch.from_numpy(flat_f32).to(self.device).to(self.tdtype)
+        assert t.numel() == self.weights.numel(), (t.numel(), self.weights.numel())
+        self.weights.copy_(t)
+
+    def set_io(self, mb, x, dy):
+        """x, dy: torch tensors [M, H] of the stage dtype on the device; allocates y and dx."""
+        y = self.torch.empty_like(x)
+        dx = self.torch.empty_like(x)
+        self.io[mb] = (x, y, dy, dx)
+        check(lib().chimera_stage_set_io(self.handle, mb, _ptr(x), _ptr(y), _ptr(dy), _ptr(dx)))
+        return y, dx
+
+    def fwd(self, mb):
+        check(lib().chimera_fwd(self.handle, mb))
+
+    def bwd(self, mb):
+        check(lib().chimera_bwd(self.handle, mb))
+
+    def zero_grads(self):
+        check(lib().chimera_stage_zero_grads(self.handle))
+
+    def read_grads(self):
+        import numpy as np
+        out = np.empty(self.grads.numel(), dtype=np.float32)
+        check(lib().chimera_stage_read_grads(self.handle, out.ctypes.data_as(C.c_void_p), out.nbytes))
+        return out
+
+    def close(self):
+        if self.handle:
+            lib().chimera_stage_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def chimera_worker_bind(down, up):
+    check(lib().chimera_worker_bind(down.handle, up.handle if up is not None else None))
+
+
+def chimera_run_worker(rank, D, N):
+    check(lib().chimera_run_worker(rank, D, N))
+
+
+def chimera_run_worker_algo(algo, rank, D, N):
+    check(lib().chimera_run_worker_algo(algo, rank, D, N))
+
+
+def chimera_worker_set_timing(on):
+    check(lib().chimera_worker_set_timing(int(on)))
+
+
+def chimera_worker_last_timing():
+    f, b, nf, nb = C.c_double(), C.c_double(), C.c_int(), C.c_int()
+    check(lib().chimera_worker_last_timing(C.byref(f), C.byref(b), C.byref(nf), C.byref(nb)))
+    return dict(fwd_ms=f.value, bwd_ms=b.value, n_fwd=nf.value, n_bwd=nb.value)
+
+
+def stash_slots_needed(algo, D, N, rank):
+    """Slots each of the worker's two stages needs: (down, up)."""
+    need = [0, 0]
+    for op in chimera_schedule(algo, D, N, rank):
+        need[op.pipe] = max(need[op.pipe], op.slot + 1)
+    return tuple(need)
+
+
+# ---------------------------------------------------------- single operators
+def _stream(t):
+    import torch
+    return C.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _dt(t):
+    import torch
+    return F32 if t.dtype == torch.float32 else BF16
+
+
+def chimera_op_gemm(a, b, c, m, n, k, a_kc, b_kc, epilogue=EPI_NONE, bias=None, r=None, c2=None, impl=0,
+                    gelu_erf=False, lda=None, ldb=None):
+    lda = lda if lda is not None else (k if a_kc else m)
+    ldb = ldb if ldb is not None else (k if b_kc else n)
+    check(lib().chimera_op_gemm(_dt(a), impl, epilogue, int(gelu_erf), m, n, k, _ptr(a), lda, int(a_kc), _ptr(b), ldb,
+                                int(b_kc), _ptr(bias), _ptr(r), _ptr(c), _ptr(c2), _stream(a)))
+
+
+def chimera_op_layernorm_fwd(x, gamma, beta, y, mean, rstd):
+    rows, cols = x.shape
+    check(lib().chimera_op_layernorm_fwd(_dt(x), rows, cols, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(mean),
+                                         _ptr(rstd), _stream(x)))
+
+
+def chimera_op_layernorm_bwd(dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta):
+    import torch
+    rows, cols = x.shape
+    scratch = torch.empty(lib().chimera_op_layernorm_bwd_scratch_floats(rows, cols), dtype=torch.float32, device=x.device)
+    check(lib().chimera_op_layernorm_bwd(_dt(x), rows, cols, _ptr(dy), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma),
+                                         _ptr(res), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), _stream(x)))
+
+
+def chimera_op_colsum(x, out):
+    import torch
+    rows, cols = x.shape
+    scratch = torch.empty(lib().chimera_op_colsum_scratch_floats(rows, cols), dtype=torch.float32, device=x.device)
+    check(lib().chimera_op_colsum(_dt(x), rows, cols, _ptr(x), _ptr(out), _ptr(scratch), _stream(x)))
+
+
+def chimera_op_attention_fwd(qkv, ctx, lse, batch, seq, heads, head_dim, causal, impl=0):
+    check(lib().chimera_op_attention_fwd(_dt(qkv), impl, batch, seq, heads, head_dim, int(causal), _ptr(qkv), _ptr(ctx),
+                                         _ptr(lse), _stream(qkv)))
+
+
+def chimera_op_attention_bwd(qkv, ctx, lse, dctx, dqkv, delta, batch, seq, heads, head_dim, causal, impl=0):
+    check(lib().chimera_op_attention_bwd(_dt(qkv), impl, batch, seq, heads, head_dim, int(causal), _ptr(qkv), _ptr(ctx),
+                                         _ptr(lse), _ptr(dctx), _ptr(dqkv), _ptr(delta), _stream(qkv)))

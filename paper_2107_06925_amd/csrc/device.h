@@ -1,0 +1,85 @@
+// Device-side helpers shared by the HIP kernels: element types, 16-byte
+// vector access, wavefront reductions (64 lanes) and the GeLU forms.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+
+namespace chimera {
+
+typedef __bf16 bf16_t;
+
+constexpr float LN_EPS = 1e-5f;
+constexpr int WAVE = 64;
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int VEC = 4;   // elements per 16-byte access
+    static __device__ __forceinline__ float to_f(float v) { return v; }
+    static __device__ __forceinline__ float from_f(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float to_f(bf16_t v) { return (float)v; }
+    static __device__ __forceinline__ bf16_t from_f(float v) { return (bf16_t)v; }   // nearest even
+};
+
+// 16-byte load of Elem<T>::VEC consecutive elements, widened to float.
+template <typename T> __device__ __forceinline__ void load_vec(const T* p, float* out);
+template <> __device__ __forceinline__ void load_vec<float>(const float* p, float* out) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <> __device__ __forceinline__ void load_vec<bf16_t>(const bf16_t* p, float* out) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(w[i] << 16);
+        out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+template <typename T> __device__ __forceinline__ void store_vec(T* p, const float* in);
+template <> __device__ __forceinline__ void store_vec<float>(float* p, const float* in) {
+    *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+}
+template <> __device__ __forceinline__ void store_vec<bf16_t>(bf16_t* p, const float* in) {
+    typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (bf16_t)in[i];
+    *reinterpret_cast<bf16x8*>(p) = v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+
+// GeLU, tanh form: 0.5 u (1 + tanh(sqrt(2/pi) (u + 0.044715 u^3))); erf form: u Phi(u).
+__device__ __forceinline__ float gelu_f(float u, int erf_form) {
+    if (erf_form) return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f));
+    const float t = tanhf(0.79788456080286536f * (u + 0.044715f * u * u * u));
+    return 0.5f * u * (1.0f + t);
+}
+__device__ __forceinline__ float gelu_grad_f(float u, int erf_form) {
+    if (erf_form)
+        return 0.5f * (1.0f + erff(u * 0.70710678118654752f)) + u * __expf(-0.5f * u * u) * 0.39894228040143268f;
+    const float t = tanhf(0.79788456080286536f * (u + 0.044715f * u * u * u));
+    return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * 0.79788456080286536f * (1.0f + 3.0f * 0.044715f * u * u);
+}
+
+#define CHIMERA_LAUNCH_CHECK(what)                                                           \
+    do {                                                                                     \
+        hipError_t e__ = hipGetLastError();                                                  \
+        if (e__ != hipSuccess) return fail(CHIMERA_EDEVICE, "%s: %s", what, hipGetErrorString(e__)); \
+    } while (0)
+
+}  // namespace chimera

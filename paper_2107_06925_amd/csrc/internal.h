@@ -1,0 +1,84 @@
+// Declarations shared by the library's translation units (host side).
+#pragma once
+
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/chimera.h"
+
+namespace chimera {
+
+using Op = chimera_op;
+
+// Records the message for chimera_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+struct ReplayStats {
+    int64_t makespan = 0;
+    std::vector<int64_t> bubbles;
+    std::vector<int32_t> stash_peak;
+    int32_t cf = 0, cb = 0;
+};
+
+int build_schedule(int algo, int D, int N, std::vector<std::vector<Op>>& lists);
+int replay(const std::vector<std::vector<Op>>& lists, int D, int N, int64_t cost_f, int64_t cost_b,
+           std::vector<std::vector<int64_t>>& start, ReplayStats* stats);
+int annotate(std::vector<std::vector<Op>>& lists, int D, int N);
+
+// ------------------------------------------------------------------ kernels
+// Every launcher enqueues on `stream` (a hipStream_t as void*) and returns a
+// CHIMERA_* code; shapes are validated here, on the host, before any launch.
+
+enum Epilogue {
+    EPI_NONE = 0,           // C = acc
+    EPI_BIAS = 1,           // C = acc + bias[n]
+    EPI_BIAS_GELU = 2,      // C = acc + bias[n], C2 = GeLU(C)
+    EPI_BIAS_RESIDUAL = 3,  // C = acc + bias[n] + R[m,n]
+    EPI_DGELU = 4,          // C = acc * GeLU'(R[m,n])
+    EPI_ACCUM_F32 = 5       // C (float) += acc
+};
+
+struct GemmArgs {
+    int m, n, k;
+    const void* a; int lda; int a_kc;   // a_kc: A stored [m,k]; else [k,m]
+    const void* b; int ldb; int b_kc;   // b_kc: B stored [n,k]; else [k,n]
+    const void* bias;                   // [n], stage dtype
+    const void* r;                      // [m,n], stage dtype
+    void* c;                            // [m,n]
+    void* c2;                           // [m,n]
+    int epilogue;
+    int gelu_erf;
+};
+
+int gemm_reference(int dtype, const GemmArgs& g, void* stream);
+int gemm_mfma_bf16(const GemmArgs& g, void* stream);
+bool gemm_mfma_supports(const GemmArgs& g);
+
+int layernorm_fwd(int dtype, int rows, int cols, const void* x, const void* gamma, const void* beta,
+                  void* y, float* mean, float* rstd, void* stream);
+size_t layernorm_bwd_scratch_floats(int rows, int cols);
+int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, const float* mean,
+                  const float* rstd, const void* gamma, const void* res, void* dx, float* dgamma,
+                  float* dbeta, float* scratch, void* stream);
+size_t colsum_scratch_floats(int rows, int cols);
+int colsum(int dtype, int rows, int cols, const void* x, float* out, float* scratch, void* stream);
+int fill_zero_f32(float* p, size_t n, void* stream);
+
+struct AttnArgs {
+    int batch, seq, heads, head_dim, causal;
+    const void* qkv;      // [M, 3H]
+    void* ctx;            // fwd out / bwd in [M, H]
+    float* lse;           // [batch, heads, seq]
+    const void* dctx;     // bwd [M, H]
+    void* dqkv;           // bwd [M, 3H]
+    float* delta;         // bwd scratch [batch, heads, seq]
+};
+int attention_fwd_reference(int dtype, const AttnArgs& a, void* stream);
+int attention_bwd_reference(int dtype, const AttnArgs& a, void* stream);
+bool attention_mfma_supports(const AttnArgs& a);
+int attention_fwd_mfma(const AttnArgs& a, void* stream);
+int attention_bwd_mfma(const AttnArgs& a, void* stream);
+
+}  // namespace chimera

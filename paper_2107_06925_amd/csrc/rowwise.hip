@@ -1,0 +1,327 @@
+// HBM-bound kernels of a Transformer block: LayerNorm forward and backward,
+// column sums (bias gradients), partial-sum reduction and fill.  One 64-lane
+// wavefront owns a row; every access is a 16-byte vector, lanes side by side,
+// so a wavefront reads 1 KiB contiguous per step.  Column reductions are
+// two-phase (per-block partials, then a fixed-order sum) so that results do
+// not depend on scheduling.
+#include "device.h"
+
+namespace chimera {
+
+namespace {
+
+constexpr int LN_WAVES = 4;        // wavefronts (rows in flight) per block
+constexpr int LNB_ROWS = 16;       // rows per block in the LayerNorm backward
+constexpr int CS_ROWS = 64;        // rows per block in the column sum
+
+// ------------------------------------------------------------- LayerNorm fwd
+// y = (x - mean) * rstd * gamma + beta, biased variance, eps 1e-5.
+// T chunks per lane are kept in registers between the passes.
+template <typename T, int MAXT>
+__global__ __launch_bounds__(LN_WAVES* WAVE) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                                const T* __restrict__ beta, T* __restrict__ y,
+                                                                float* __restrict__ mean, float* __restrict__ rstd,
+                                                                int rows, int cols) {
+    constexpr int V = Elem<T>::VEC;
+    const int lane = threadIdx.x % WAVE;
+    const int row = blockIdx.x * LN_WAVES + threadIdx.x / WAVE;
+    if (row >= rows) return;
+    const int nchunk = cols / V;
+    const T* xr = x + (size_t)row * cols;
+    float v[MAXT][V];
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < MAXT; ++t) {
+        const int c = lane + t * WAVE;
+        if (c < nchunk) {
+            load_vec<T>(xr + c * V, v[t]);
+#pragma unroll
+            for (int e = 0; e < V; ++e) s += v[t][e];
+        }
+    }
+    const float mu = wave_sum(s) / (float)cols;
+    float q = 0.f;
+#pragma unroll
+    for (int t = 0; t < MAXT; ++t) {
+        const int c = lane + t * WAVE;
+        if (c < nchunk) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) { const float d = v[t][e] - mu; q += d * d; }
+        }
+    }
+    const float rs = 1.0f / sqrtf(wave_sum(q) / (float)cols + LN_EPS);
+    if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+    T* yr = y + (size_t)row * cols;
+#pragma unroll
+    for (int t = 0; t < MAXT; ++t) {
+        const int c = lane + t * WAVE;
+        if (c < nchunk) {
+            float g[V], b[V], o[V];
+            load_vec<T>(gamma + c * V, g);
+            load_vec<T>(beta + c * V, b);
+#pragma unroll
+            for (int e = 0; e < V; ++e) o[e] = (v[t][e] - mu) * rs * g[e] + b[e];
+            store_vec<T>(yr + c * V, o);
+        }
+    }
+}
+
+// ------------------------------------------------------------- LayerNorm bwd
+// With xhat = (x - mean) rstd and dxhat = dy * gamma:
+//   dx = res + rstd * (dxhat - mean_c(dxhat) - xhat * mean_c(dxhat * xhat))
+//   dgamma += sum_rows dy * xhat,  dbeta += sum_rows dy.
+// A block takes LNB_ROWS rows; every lane owns fixed columns, so the column
+// sums accumulate in registers, are combined over the block's wavefronts in
+// LDS in a fixed order and leave as one partial row per block:
+// partial[block][0][cols] = dgamma part, partial[block][1][cols] = dbeta part.
+template <typename T, int MAXT>
+__global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                                const float* __restrict__ mean,
+                                                                const float* __restrict__ rstd,
+                                                                const T* __restrict__ gamma, const T* __restrict__ res,
+                                                                T* __restrict__ dx, float* __restrict__ partial,
+                                                                int rows, int cols) {
+    constexpr int V = Elem<T>::VEC;
+    extern __shared__ float red[];   // [2][cols]
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    const int nchunk = cols / V;
+    float ag[MAXT][V], ab[MAXT][V], g[MAXT][V];
+#pragma unroll
+    for (int t = 0; t < MAXT; ++t) {
+        const int c = lane + t * WAVE;
+#pragma unroll
+        for (int e = 0; e < V; ++e) { ag[t][e] = 0.f; ab[t][e] = 0.f; g[t][e] = 0.f; }
+        if (c < nchunk) load_vec<T>(gamma + c * V, g[t]);
+    }
+    const int row0 = blockIdx.x * LNB_ROWS;
+    for (int r = wave; r < LNB_ROWS; r += LN_WAVES) {
+        const int row = row0 + r;
+        if (row >= rows) break;
+        const float mu = mean[row], rs = rstd[row];
+        float dxh[MAXT][V], xh[MAXT][V];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) {
+            const int c = lane + t * WAVE;
+            if (c < nchunk) {
+                float d[V], xv[V];
+                load_vec<T>(dy + (size_t)row * cols + c * V, d);
+                load_vec<T>(x + (size_t)row * cols + c * V, xv);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    xh[t][e] = (xv[e] - mu) * rs;
+                    dxh[t][e] = d[e] * g[t][e];
+                    s1 += dxh[t][e];
+                    s2 += dxh[t][e] * xh[t][e];
+                    ag[t][e] += d[e] * xh[t][e];
+                    ab[t][e] += d[e];
+                }
+            }
+        }
+        const float m1 = wave_sum(s1) / (float)cols;
+        const float m2 = wave_sum(s2) / (float)cols;
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) {
+            const int c = lane + t * WAVE;
+            if (c < nchunk) {
+                float rv[V], o[V];
+                load_vec<T>(res + (size_t)row * cols + c * V, rv);
+#pragma unroll
+                for (int e = 0; e < V; ++e) o[e] = rv[e] + rs * (dxh[t][e] - m1 - xh[t][e] * m2);
+                store_vec<T>(dx + (size_t)row * cols + c * V, o);
+            }
+        }
+    }
+    // fixed-order combination over the wavefronts of the block
+    for (int w = 0; w < LN_WAVES; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int t = 0; t < MAXT; ++t) {
+                const int c = lane + t * WAVE;
+                if (c < nchunk) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        const int col = c * V + e;
+                        if (w == 0) { red[col] = ag[t][e]; red[cols + col] = ab[t][e]; }
+                        else { red[col] += ag[t][e]; red[cols + col] += ab[t][e]; }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    float* out = partial + (size_t)blockIdx.x * 2 * cols;
+    for (int i = threadIdx.x; i < 2 * cols; i += LN_WAVES * WAVE) out[i] = red[i];
+}
+
+// ---------------------------------------------------------------- column sum
+// partial[blockIdx.y][cols] = sum of CS_ROWS rows of x; lanes own columns.
+template <typename T>
+__global__ __launch_bounds__(LN_WAVES* WAVE) void colsum_kernel(const T* __restrict__ x, float* __restrict__ partial,
+                                                                int rows, int cols) {
+    constexpr int V = Elem<T>::VEC;
+    __shared__ float red[WAVE * V];
+    const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+    const int c = blockIdx.x * WAVE + lane;     // chunk of V columns
+    const bool live = c < cols / V;
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    const int row0 = blockIdx.y * CS_ROWS;
+    const int row1 = min(rows, row0 + CS_ROWS);
+    if (live)
+        for (int row = row0 + wave; row < row1; row += LN_WAVES) {
+            float v[V];
+            load_vec<T>(x + (size_t)row * cols + c * V, v);
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += v[e];
+        }
+    for (int w = 0; w < LN_WAVES; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                if (w == 0) red[lane * V + e] = acc[e];
+                else red[lane * V + e] += acc[e];
+            }
+        }
+        __syncthreads();
+    }
+    if (wave == 0 && live) {
+        float* out = partial + (size_t)blockIdx.y * cols + c * V;
+#pragma unroll
+        for (int e = 0; e < V; ++e) out[e] = red[lane * V + e];
+    }
+}
+
+// out[i] += sum_p partial[p][i], p ascending.
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int n, float* __restrict__ out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int p = 0; p < nparts; ++p) s += partial[(size_t)p * n + i];
+    out[i] += s;
+}
+
+// LayerNorm backward partials hold [block][2][cols]; dgamma and dbeta are separate arrays.
+__global__ void reduce_ln_partials_kernel(const float* __restrict__ partial, int nparts, int cols,
+                                          float* __restrict__ dgamma, float* __restrict__ dbeta) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 2 * cols) return;
+    float s = 0.f;
+    for (int p = 0; p < nparts; ++p) s += partial[(size_t)p * 2 * cols + i];
+    if (i < cols) dgamma[i] += s; else dbeta[i - cols] += s;
+}
+
+__global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4, float* __restrict__ tail, int ntail) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0.f;
+}
+
+template <typename T>
+int ln_fwd_launch(int rows, int cols, const void* x, const void* gamma, const void* beta, void* y, float* mean,
+                  float* rstd, hipStream_t s) {
+    constexpr int V = Elem<T>::VEC;
+    const int per_lane = (cols / V + WAVE - 1) / WAVE;
+    const dim3 grid((rows + LN_WAVES - 1) / LN_WAVES), block(LN_WAVES * WAVE);
+#define LN_FWD_CASE(N)                                                                                        \
+    hipLaunchKernelGGL((ln_fwd_kernel<T, N>), grid, block, 0, s, (const T*)x, (const T*)gamma, (const T*)beta, \
+                       (T*)y, mean, rstd, rows, cols)
+    if (per_lane <= 1) LN_FWD_CASE(1);
+    else if (per_lane <= 2) LN_FWD_CASE(2);
+    else if (per_lane <= 4) LN_FWD_CASE(4);
+    else if (per_lane <= 8) LN_FWD_CASE(8);
+    else return fail(CHIMERA_EINVAL, "LayerNorm width %d too large (max %d)", cols, 8 * WAVE * V);
+#undef LN_FWD_CASE
+    CHIMERA_LAUNCH_CHECK("layernorm forward");
+    return CHIMERA_OK;
+}
+
+template <typename T>
+int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
+                  const void* gamma, const void* res, void* dx, float* dgamma, float* dbeta, float* scratch,
+                  hipStream_t s) {
+    constexpr int V = Elem<T>::VEC;
+    const int per_lane = (cols / V + WAVE - 1) / WAVE;
+    const int nblk = (rows + LNB_ROWS - 1) / LNB_ROWS;
+    const dim3 grid(nblk), block(LN_WAVES * WAVE);
+    const size_t lds = (size_t)2 * cols * sizeof(float);
+#define LN_BWD_CASE(N)                                                                                       \
+    hipLaunchKernelGGL((ln_bwd_kernel<T, N>), grid, block, lds, s, (const T*)dy, (const T*)x, mean, rstd,    \
+                       (const T*)gamma, (const T*)res, (T*)dx, scratch, rows, cols)
+    if (per_lane <= 1) LN_BWD_CASE(1);
+    else if (per_lane <= 2) LN_BWD_CASE(2);
+    else if (per_lane <= 4) LN_BWD_CASE(4);
+    else if (per_lane <= 8) LN_BWD_CASE(8);
+    else return fail(CHIMERA_EINVAL, "LayerNorm width %d too large for the backward (max %d)", cols, 8 * WAVE * V);
+#undef LN_BWD_CASE
+    CHIMERA_LAUNCH_CHECK("layernorm backward");
+    hipLaunchKernelGGL(reduce_ln_partials_kernel, dim3((2 * cols + 255) / 256), dim3(256), 0, s, scratch, nblk, cols,
+                       dgamma, dbeta);
+    CHIMERA_LAUNCH_CHECK("layernorm backward reduce");
+    return CHIMERA_OK;
+}
+
+template <typename T>
+int colsum_launch(int rows, int cols, const void* x, float* out, float* scratch, hipStream_t s) {
+    constexpr int V = Elem<T>::VEC;
+    const int nparts = (rows + CS_ROWS - 1) / CS_ROWS;
+    const dim3 grid((cols / V + WAVE - 1) / WAVE, nparts), block(LN_WAVES * WAVE);
+    hipLaunchKernelGGL((colsum_kernel<T>), grid, block, 0, s, (const T*)x, scratch, rows, cols);
+    CHIMERA_LAUNCH_CHECK("column sum");
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, scratch, nparts, cols, out);
+    CHIMERA_LAUNCH_CHECK("column sum reduce");
+    return CHIMERA_OK;
+}
+
+int check_rowwise(int dtype, int rows, int cols) {
+    if (dtype != CHIMERA_F32 && dtype != CHIMERA_BF16) return fail(CHIMERA_EINVAL, "unknown dtype %d", dtype);
+    if (rows < 1 || cols < 1) return fail(CHIMERA_EINVAL, "rows=%d cols=%d must be positive", rows, cols);
+    if (cols % 8) return fail(CHIMERA_EINVAL, "cols=%d must be a multiple of 8", cols);
+    return CHIMERA_OK;
+}
+
+}  // namespace
+
+int layernorm_fwd(int dtype, int rows, int cols, const void* x, const void* gamma, const void* beta, void* y,
+                  float* mean, float* rstd, void* stream) {
+    if (int rc = check_rowwise(dtype, rows, cols)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    return dtype == CHIMERA_F32 ? ln_fwd_launch<float>(rows, cols, x, gamma, beta, y, mean, rstd, s)
+                                : ln_fwd_launch<bf16_t>(rows, cols, x, gamma, beta, y, mean, rstd, s);
+}
+
+size_t layernorm_bwd_scratch_floats(int rows, int cols) {
+    return (size_t)((rows + LNB_ROWS - 1) / LNB_ROWS) * 2 * cols;
+}
+
+int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
+                  const void* gamma, const void* res, void* dx, float* dgamma, float* dbeta, float* scratch,
+                  void* stream) {
+    if (int rc = check_rowwise(dtype, rows, cols)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    return dtype == CHIMERA_F32
+               ? ln_bwd_launch<float>(rows, cols, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, scratch, s)
+               : ln_bwd_launch<bf16_t>(rows, cols, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, scratch, s);
+}
+
+size_t colsum_scratch_floats(int rows, int cols) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * cols; }
+
+int colsum(int dtype, int rows, int cols, const void* x, float* out, float* scratch, void* stream) {
+    if (int rc = check_rowwise(dtype, rows, cols)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    return dtype == CHIMERA_F32 ? colsum_launch<float>(rows, cols, x, out, scratch, s)
+                                : colsum_launch<bf16_t>(rows, cols, x, out, scratch, s);
+}
+
+int fill_zero_f32(float* p, size_t n, void* stream) {
+    if (!n) return CHIMERA_OK;
+    const size_t n4 = n / 4;
+    const int ntail = (int)(n - n4 * 4);
+    const int blocks = (int)std::min<size_t>((n4 + 255) / 256 + 1, 4096);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (float4*)p, n4, p + n4 * 4, ntail);
+    CHIMERA_LAUNCH_CHECK("fill");
+    return CHIMERA_OK;
+}
+
+}  // namespace chimera

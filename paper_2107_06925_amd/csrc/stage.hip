@@ -1,0 +1,509 @@
+// Stage runtime and C ABI: a stage of L Transformer blocks (forward, backward
+// with in-place float gradient accumulation), its activation stash, and the
+// replay of a worker's op list (section 3.1: worker i runs stage i of the down
+// pipeline and stage D-1-i of the up pipeline in the merged 1F1B order).
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <unordered_map>
+#include <vector>
+
+#include "internal.h"
+
+namespace chimera {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+}  // namespace chimera
+
+using namespace chimera;
+
+struct chimera_stage {
+    int L, H, heads, S, B, dtype;
+    int M, d;
+    size_t esz;
+    int causal = 1, gelu_erf = 0, kernels = 0;
+    bool bound = false;
+
+    // parameter offsets (elements) inside one block and block size
+    size_t o_ln1_g, o_ln1_b, o_w_qkv, o_b_qkv, o_w_o, o_b_o, o_ln2_g, o_ln2_b, o_w_fc1, o_b_fc1, o_w_fc2, o_b_fc2;
+    size_t layer_params;
+
+    // stash layout (bytes) inside one block of one slot
+    size_t s_mean1, s_rstd1, s_h1, s_qkv, s_ctx, s_lse, s_x1, s_mean2, s_rstd2, s_h2, s_u, s_g, s_y;
+    size_t layer_stash, slot_bytes;
+
+    // workspace layout (bytes)
+    size_t w_dy[2], w_du, w_dh, w_dx1, w_dctx, w_dqkv, w_delta, w_scratch, ws_bytes;
+
+    const char* weights = nullptr;
+    float* grads = nullptr;
+    char* stash = nullptr;
+    char* ws = nullptr;
+    int slots = 0;
+    hipStream_t stream = nullptr;
+
+    struct IO { const void* x; void* y; const void* dy; void* dx; };
+    std::unordered_map<int, IO> io;
+    std::unordered_map<int, int> in_flight;   // micro-batch -> slot
+    std::vector<char> slot_used;
+
+    const char* W(int l, size_t off) const { return weights + ((size_t)l * layer_params + off) * esz; }
+    float* G(int l, size_t off) const { return grads + (size_t)l * layer_params + off; }
+    char* ST(int slot, int l, size_t off) const { return stash + (size_t)slot * slot_bytes + (size_t)l * layer_stash + off; }
+};
+
+namespace {
+
+void layout(chimera_stage* st) {
+    const size_t H = st->H, M = st->M, e = st->esz;
+    size_t o = 0;
+    auto take = [&](size_t n) { size_t r = o; o += n; return r; };
+    st->o_ln1_g = take(H); st->o_ln1_b = take(H);
+    st->o_w_qkv = take(H * 3 * H); st->o_b_qkv = take(3 * H);
+    st->o_w_o = take(H * H); st->o_b_o = take(H);
+    st->o_ln2_g = take(H); st->o_ln2_b = take(H);
+    st->o_w_fc1 = take(H * 4 * H); st->o_b_fc1 = take(4 * H);
+    st->o_w_fc2 = take(4 * H * H); st->o_b_fc2 = take(H);
+    st->layer_params = o;
+
+    size_t b = 0;
+    auto takeb = [&](size_t bytes) { size_t r = b; b += align_up(bytes); return r; };
+    st->s_mean1 = takeb(M * 4); st->s_rstd1 = takeb(M * 4);
+    st->s_h1 = takeb(M * H * e);
+    st->s_qkv = takeb(M * 3 * H * e);
+    st->s_ctx = takeb(M * H * e);
+    st->s_lse = takeb((size_t)st->B * st->heads * st->S * 4);
+    st->s_x1 = takeb(M * H * e);
+    st->s_mean2 = takeb(M * 4); st->s_rstd2 = takeb(M * 4);
+    st->s_h2 = takeb(M * H * e);
+    st->s_u = takeb(M * 4 * H * e);
+    st->s_g = takeb(M * 4 * H * e);
+    st->s_y = takeb(M * H * e);
+    st->layer_stash = b;
+    st->slot_bytes = b * st->L;
+
+    b = 0;
+    st->w_dy[0] = takeb(M * H * e); st->w_dy[1] = takeb(M * H * e);
+    st->w_du = takeb(M * 4 * H * e);
+    st->w_dh = takeb(M * H * e);
+    st->w_dx1 = takeb(M * H * e);
+    st->w_dctx = takeb(M * H * e);
+    st->w_dqkv = takeb(M * 3 * H * e);
+    st->w_delta = takeb((size_t)st->B * st->heads * st->S * 4);
+    const size_t sc = std::max(colsum_scratch_floats((int)M, (int)(4 * H)), layernorm_bwd_scratch_floats((int)M, (int)H));
+    st->w_scratch = takeb(sc * 4);
+    st->ws_bytes = b;
+}
+
+int gemm(chimera_stage* st, const GemmArgs& g) {
+    if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_supports(g)) return gemm_mfma_bf16(g, st->stream);
+    return gemm_reference(st->dtype, g, st->stream);
+}
+
+// C[m,n] = X[m,k] W[k,n] (+ epilogue); W stored [in, out].
+int linear_fwd(chimera_stage* st, int m, int n, int k, const void* x, const void* w, const void* bias, const void* r,
+               void* c, void* c2, int epi) {
+    GemmArgs g{};
+    g.m = m; g.n = n; g.k = k;
+    g.a = x; g.lda = k; g.a_kc = 1;
+    g.b = w; g.ldb = n; g.b_kc = 0;
+    g.bias = bias; g.r = r; g.c = c; g.c2 = c2; g.epilogue = epi; g.gelu_erf = st->gelu_erf;
+    return gemm(st, g);
+}
+// dX[m,k] = dY[m,n] W^T, W stored [k, n]: contraction over n, contiguous in both.
+int linear_dgrad(chimera_stage* st, int m, int n, int k, const void* dy, const void* w, const void* r, void* dx, int epi) {
+    GemmArgs g{};
+    g.m = m; g.n = k; g.k = n;
+    g.a = dy; g.lda = n; g.a_kc = 1;
+    g.b = w; g.ldb = n; g.b_kc = 1;
+    g.r = r; g.c = dx; g.epilogue = epi; g.gelu_erf = st->gelu_erf;
+    return gemm(st, g);
+}
+// dW[k,n] += X[m,k]^T dY[m,n]: contraction over the tokens.
+int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const void* dy, float* dw) {
+    GemmArgs g{};
+    g.m = k; g.n = n; g.k = m;
+    g.a = x; g.lda = k; g.a_kc = 0;
+    g.b = dy; g.ldb = n; g.b_kc = 0;
+    g.c = dw; g.epilogue = EPI_ACCUM_F32;
+    return gemm(st, g);
+}
+
+int attn_args(chimera_stage* st, AttnArgs& a) {
+    a.batch = st->B; a.seq = st->S; a.heads = st->heads; a.head_dim = st->d; a.causal = st->causal;
+    return 0;
+}
+
+#define TRY(expr) do { int rc__ = (expr); if (rc__) return rc__; } while (0)
+
+int stage_forward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
+    const int M = st->M, H = st->H, L = st->L;
+    void* s = st->stream;
+    for (int l = 0; l < L; ++l) {
+        const void* x = l == 0 ? io.x : st->ST(slot, l - 1, st->s_y);
+        void* y = l == L - 1 ? io.y : st->ST(slot, l, st->s_y);
+        void* h1 = st->ST(slot, l, st->s_h1);
+        void* qkv = st->ST(slot, l, st->s_qkv);
+        void* ctx = st->ST(slot, l, st->s_ctx);
+        void* x1 = st->ST(slot, l, st->s_x1);
+        void* h2 = st->ST(slot, l, st->s_h2);
+        void* u = st->ST(slot, l, st->s_u);
+        void* g = st->ST(slot, l, st->s_g);
+        TRY(layernorm_fwd(st->dtype, M, H, x, st->W(l, st->o_ln1_g), st->W(l, st->o_ln1_b), h1,
+                          (float*)st->ST(slot, l, st->s_mean1), (float*)st->ST(slot, l, st->s_rstd1), s));
+        TRY(linear_fwd(st, M, 3 * H, H, h1, st->W(l, st->o_w_qkv), st->W(l, st->o_b_qkv), nullptr, qkv, nullptr, EPI_BIAS));
+        AttnArgs a{};
+        attn_args(st, a);
+        a.qkv = qkv; a.ctx = ctx; a.lse = (float*)st->ST(slot, l, st->s_lse);
+        if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && attention_mfma_supports(a)) TRY(attention_fwd_mfma(a, s));
+        else TRY(attention_fwd_reference(st->dtype, a, s));
+        TRY(linear_fwd(st, M, H, H, ctx, st->W(l, st->o_w_o), st->W(l, st->o_b_o), x, x1, nullptr, EPI_BIAS_RESIDUAL));
+        TRY(layernorm_fwd(st->dtype, M, H, x1, st->W(l, st->o_ln2_g), st->W(l, st->o_ln2_b), h2,
+                          (float*)st->ST(slot, l, st->s_mean2), (float*)st->ST(slot, l, st->s_rstd2), s));
+        TRY(linear_fwd(st, M, 4 * H, H, h2, st->W(l, st->o_w_fc1), st->W(l, st->o_b_fc1), nullptr, u, g, EPI_BIAS_GELU));
+        TRY(linear_fwd(st, M, H, 4 * H, g, st->W(l, st->o_w_fc2), st->W(l, st->o_b_fc2), x1, y, nullptr, EPI_BIAS_RESIDUAL));
+    }
+    return CHIMERA_OK;
+}
+
+int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
+    const int M = st->M, H = st->H, L = st->L;
+    void* s = st->stream;
+    float* scratch = (float*)(st->ws + st->w_scratch);
+    void* du = st->ws + st->w_du;
+    void* dh = st->ws + st->w_dh;
+    void* dx1 = st->ws + st->w_dx1;
+    void* dctx = st->ws + st->w_dctx;
+    void* dqkv = st->ws + st->w_dqkv;
+    const void* dy = io.dy;
+    for (int l = L - 1; l >= 0; --l) {
+        const void* x = l == 0 ? io.x : st->ST(slot, l - 1, st->s_y);
+        void* dx = l == 0 ? io.dx : (void*)(st->ws + st->w_dy[l & 1]);
+        const void* h1 = st->ST(slot, l, st->s_h1);
+        const void* qkv = st->ST(slot, l, st->s_qkv);
+        const void* ctx = st->ST(slot, l, st->s_ctx);
+        const void* x1 = st->ST(slot, l, st->s_x1);
+        const void* h2 = st->ST(slot, l, st->s_h2);
+        const void* u = st->ST(slot, l, st->s_u);
+        const void* g = st->ST(slot, l, st->s_g);
+        // y = x1 + g W2 + b2
+        TRY(colsum(st->dtype, M, H, dy, st->G(l, st->o_b_fc2), scratch, s));
+        TRY(linear_wgrad(st, M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2)));
+        TRY(linear_dgrad(st, M, H, 4 * H, dy, st->W(l, st->o_w_fc2), u, du, EPI_DGELU));       // du = dg * GeLU'(u)
+        // u = h2 W1 + b1
+        TRY(colsum(st->dtype, M, 4 * H, du, st->G(l, st->o_b_fc1), scratch, s));
+        TRY(linear_wgrad(st, M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1)));
+        TRY(linear_dgrad(st, M, 4 * H, H, du, st->W(l, st->o_w_fc1), nullptr, dh, EPI_NONE));
+        TRY(layernorm_bwd(st->dtype, M, H, dh, x1, (const float*)st->ST(slot, l, st->s_mean2),
+                          (const float*)st->ST(slot, l, st->s_rstd2), st->W(l, st->o_ln2_g), dy, dx1,
+                          st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch, s));
+        // x1 = x + ctx Wo + bo
+        TRY(colsum(st->dtype, M, H, dx1, st->G(l, st->o_b_o), scratch, s));
+        TRY(linear_wgrad(st, M, H, H, ctx, dx1, st->G(l, st->o_w_o)));
+        TRY(linear_dgrad(st, M, H, H, dx1, st->W(l, st->o_w_o), nullptr, dctx, EPI_NONE));
+        AttnArgs a{};
+        attn_args(st, a);
+        a.qkv = qkv; a.ctx = (void*)ctx; a.lse = (float*)st->ST(slot, l, st->s_lse);
+        a.dctx = dctx; a.dqkv = dqkv; a.delta = (float*)(st->ws + st->w_delta);
+        if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && attention_mfma_supports(a)) TRY(attention_bwd_mfma(a, s));
+        else TRY(attention_bwd_reference(st->dtype, a, s));
+        // qkv = h1 Wqkv + bqkv
+        TRY(colsum(st->dtype, M, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch, s));
+        TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv)));
+        TRY(linear_dgrad(st, M, 3 * H, H, dqkv, st->W(l, st->o_w_qkv), nullptr, dh, EPI_NONE));
+        TRY(layernorm_bwd(st->dtype, M, H, dh, x, (const float*)st->ST(slot, l, st->s_mean1),
+                          (const float*)st->ST(slot, l, st->s_rstd1), st->W(l, st->o_ln1_g), dx1, dx,
+                          st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch, s));
+        dy = dx;
+    }
+    return CHIMERA_OK;
+}
+
+struct Worker {
+    chimera_stage* down = nullptr;
+    chimera_stage* up = nullptr;
+    int timing = 0;
+    double fwd_ms = 0, bwd_ms = 0;
+    int nf = 0, nb = 0;
+} g_worker;
+
+}  // namespace
+
+// ----------------------------------------------------------------------- ABI
+extern "C" {
+
+const char* chimera_last_error(void) { return g_err; }
+
+chimera_stage* chimera_stage_create(int layers, int hidden, int heads, int seq, int microbatch, int dtype) {
+    if (layers < 1 || hidden < 1 || heads < 1 || seq < 1 || microbatch < 1) {
+        fail(CHIMERA_EINVAL, "stage sizes must be positive");
+        return nullptr;
+    }
+    if (dtype != CHIMERA_F32 && dtype != CHIMERA_BF16) { fail(CHIMERA_EINVAL, "unknown dtype %d", dtype); return nullptr; }
+    if (hidden % heads) { fail(CHIMERA_EINVAL, "hidden=%d is not a multiple of heads=%d", hidden, heads); return nullptr; }
+    if (hidden % 8) { fail(CHIMERA_EINVAL, "hidden=%d must be a multiple of 8", hidden); return nullptr; }
+    if ((int64_t)seq * microbatch > (1 << 24) || hidden > 4096) { fail(CHIMERA_EINVAL, "stage too large"); return nullptr; }
+    chimera_stage* st = new (std::nothrow) chimera_stage();
+    if (!st) { fail(CHIMERA_ENOMEM, "out of host memory"); return nullptr; }
+    st->L = layers; st->H = hidden; st->heads = heads; st->S = seq; st->B = microbatch; st->dtype = dtype;
+    st->M = seq * microbatch; st->d = hidden / heads;
+    st->esz = dtype == CHIMERA_F32 ? 4 : 2;
+    layout(st);
+    return st;
+}
+
+int chimera_stage_set_option(chimera_stage* st, int key, int value) {
+    if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
+    if (st->bound) return fail(CHIMERA_ESTATE, "options can only be set before chimera_stage_bind");
+    switch (key) {
+        case CHIMERA_OPT_CAUSAL: if (value != 0 && value != 1) break; st->causal = value; return CHIMERA_OK;
+        case CHIMERA_OPT_GELU: if (value != 0 && value != 1) break; st->gelu_erf = value; return CHIMERA_OK;
+        case CHIMERA_OPT_KERNELS: if (value != 0 && value != 1) break; st->kernels = value; return CHIMERA_OK;
+        default: return fail(CHIMERA_EINVAL, "unknown option %d", key);
+    }
+    return fail(CHIMERA_EINVAL, "bad value %d for option %d", value, key);
+}
+
+void chimera_stage_destroy(chimera_stage* st) {
+    if (g_worker.down == st) g_worker.down = nullptr;
+    if (g_worker.up == st) g_worker.up = nullptr;
+    delete st;
+}
+
+size_t chimera_stage_weight_bytes(const chimera_stage* st) { return st ? st->layer_params * st->L * st->esz : 0; }
+size_t chimera_stage_grad_bytes(const chimera_stage* st) { return st ? st->layer_params * st->L * sizeof(float) : 0; }
+size_t chimera_stage_stash_slot_bytes(const chimera_stage* st) { return st ? st->slot_bytes : 0; }
+size_t chimera_stage_workspace_bytes(const chimera_stage* st) { return st ? st->ws_bytes : 0; }
+
+int chimera_stage_bind(chimera_stage* st, const void* d_weights, float* d_grads, void* d_stash, int stash_slots,
+                       void* d_workspace, void* hip_stream) {
+    if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
+    if (!d_weights || !d_grads || !d_stash || !d_workspace) return fail(CHIMERA_EINVAL, "a device buffer is NULL");
+    if (stash_slots < 1) return fail(CHIMERA_EINVAL, "stash_slots=%d must be positive", stash_slots);
+    if (((uintptr_t)d_weights | (uintptr_t)d_grads | (uintptr_t)d_stash | (uintptr_t)d_workspace) & 255)
+        return fail(CHIMERA_EINVAL, "device buffers must be 256-byte aligned");
+    if (!st->in_flight.empty()) return fail(CHIMERA_ESTATE, "cannot rebind with micro-batches in flight");
+    st->weights = (const char*)d_weights; st->grads = d_grads; st->stash = (char*)d_stash; st->ws = (char*)d_workspace;
+    st->slots = stash_slots; st->stream = (hipStream_t)hip_stream;
+    st->slot_used.assign(stash_slots, 0);
+    st->bound = true;
+    return CHIMERA_OK;
+}
+
+int chimera_stage_set_io(chimera_stage* st, int mb, const void* d_x_in, void* d_y_out, const void* d_dy_in,
+                         void* d_dx_out) {
+    if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
+    if (mb < 0) return fail(CHIMERA_EINVAL, "micro-batch id %d is negative", mb);
+    if (!d_x_in || !d_y_out || !d_dy_in || !d_dx_out) return fail(CHIMERA_EINVAL, "an io buffer is NULL");
+    if (((uintptr_t)d_x_in | (uintptr_t)d_y_out | (uintptr_t)d_dy_in | (uintptr_t)d_dx_out) & 15)
+        return fail(CHIMERA_EINVAL, "io buffers must be 16-byte aligned");
+    if (st->in_flight.count(mb)) return fail(CHIMERA_ESTATE, "micro-batch %d is in flight", mb);
+    st->io[mb] = chimera_stage::IO{d_x_in, d_y_out, d_dy_in, d_dx_out};
+    return CHIMERA_OK;
+}
+
+int chimera_fwd_slot(chimera_stage* st, int mb, int slot) {
+    if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
+    if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
+    auto it = st->io.find(mb);
+    if (it == st->io.end()) return fail(CHIMERA_ESTATE, "io of micro-batch %d not set", mb);
+    if (st->in_flight.count(mb)) return fail(CHIMERA_ESTATE, "forward of micro-batch %d already done", mb);
+    if (slot < 0) {
+        slot = 0;
+        while (slot < st->slots && st->slot_used[slot]) ++slot;
+        if (slot == st->slots) return fail(CHIMERA_ESTATE, "no free stash slot (%d bound)", st->slots);
+    } else if (slot >= st->slots) {
+        return fail(CHIMERA_ENOMEM, "stash slot %d requested, %d bound", slot, st->slots);
+    } else if (st->slot_used[slot]) {
+        return fail(CHIMERA_ESTATE, "stash slot %d is taken", slot);
+    }
+    int rc = stage_forward(st, it->second, slot);
+    if (rc) return rc;
+    st->slot_used[slot] = 1;
+    st->in_flight[mb] = slot;
+    return CHIMERA_OK;
+}
+
+int chimera_fwd(chimera_stage* st, int mb) { return chimera_fwd_slot(st, mb, -1); }
+
+int chimera_bwd(chimera_stage* st, int mb) {
+    if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
+    if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
+    auto fl = st->in_flight.find(mb);
+    if (fl == st->in_flight.end()) return fail(CHIMERA_ESTATE, "backward of micro-batch %d without its forward", mb);
+    int rc = stage_backward(st, st->io[mb], fl->second);
+    if (rc) return rc;
+    st->slot_used[fl->second] = 0;
+    st->in_flight.erase(fl);
+    return CHIMERA_OK;
+}
+
+int chimera_stage_in_flight(const chimera_stage* st) { return st ? (int)st->in_flight.size() : 0; }
+
+int chimera_stage_zero_grads(chimera_stage* st) {
+    if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
+    if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
+    return fill_zero_f32(st->grads, st->layer_params * st->L, st->stream);
+}
+
+int chimera_stage_read_grads(chimera_stage* st, float* h_dst, size_t bytes) {
+    if (!st || !h_dst) return fail(CHIMERA_EINVAL, "NULL argument");
+    if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
+    if (bytes < chimera_stage_grad_bytes(st)) return fail(CHIMERA_ENOMEM, "destination holds %zu bytes, need %zu", bytes, chimera_stage_grad_bytes(st));
+    hipError_t e = hipMemcpyAsync(h_dst, st->grads, chimera_stage_grad_bytes(st), hipMemcpyDeviceToHost, st->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(st->stream);
+    if (e != hipSuccess) return fail(CHIMERA_EDEVICE, "gradient readback: %s", hipGetErrorString(e));
+    return CHIMERA_OK;
+}
+
+int chimera_worker_bind(chimera_stage* down_stage, chimera_stage* up_stage) {
+    if (!down_stage) return fail(CHIMERA_EINVAL, "down stage is NULL");
+    if (!down_stage->bound || (up_stage && !up_stage->bound)) return fail(CHIMERA_ESTATE, "stages must be bound first");
+    if (down_stage == up_stage) return fail(CHIMERA_EINVAL, "down and up stage must differ");
+    g_worker.down = down_stage;
+    g_worker.up = up_stage;
+    return CHIMERA_OK;
+}
+
+int chimera_worker_set_timing(int on) { g_worker.timing = on ? 1 : 0; return CHIMERA_OK; }
+
+int chimera_run_worker_algo(int algo, int rank, int D, int N) {
+    Worker& wk = g_worker;
+    if (!wk.down) return fail(CHIMERA_ESTATE, "no worker bound");
+    std::vector<std::vector<Op>> lists;
+    TRY(build_schedule(algo, D, N, lists));
+    if (rank < 0 || rank >= D) return fail(CHIMERA_EINVAL, "rank %d outside [0,%d)", rank, D);
+    TRY(annotate(lists, D, N));
+    const std::vector<Op>& ops = lists[rank];
+    chimera_stage* stage_of[2] = {wk.down, wk.up};
+    int need[2] = {0, 0};
+    for (const Op& o : ops) need[o.pipe] = std::max(need[o.pipe], o.slot + 1);
+    for (int p = 0; p < 2; ++p) {
+        if (!need[p]) continue;
+        chimera_stage* st = stage_of[p];
+        if (!st) return fail(CHIMERA_ESTATE, "schedule uses the up pipeline but no up stage is bound");
+        if (st->slots < need[p]) return fail(CHIMERA_ENOMEM, "%s stage bound with %d stash slots, schedule needs %d", p ? "up" : "down", st->slots, need[p]);
+        if (!st->in_flight.empty()) return fail(CHIMERA_ESTATE, "%s stage has micro-batches in flight", p ? "up" : "down");
+        for (const Op& o : ops)
+            if (o.pipe == p && !st->io.count(o.mb)) return fail(CHIMERA_ESTATE, "io of micro-batch %d not set on the %s stage", o.mb, p ? "up" : "down");
+    }
+    std::vector<hipEvent_t> ev;
+    if (wk.timing) {
+        ev.resize(ops.size() * 2);
+        for (auto& e : ev)
+            if (hipEventCreate(&e) != hipSuccess) return fail(CHIMERA_EDEVICE, "hipEventCreate failed");
+    }
+    int rc = CHIMERA_OK;
+    for (size_t i = 0; i < ops.size() && !rc; ++i) {
+        const Op& o = ops[i];
+        chimera_stage* st = stage_of[o.pipe];
+        if (wk.timing) (void)hipEventRecord(ev[2 * i], st->stream);
+        rc = o.kind == 0 ? chimera_fwd_slot(st, o.mb, o.slot) : chimera_bwd(st, o.mb);
+        if (wk.timing) (void)hipEventRecord(ev[2 * i + 1], st->stream);
+    }
+    hipError_t e = hipStreamSynchronize(wk.down->stream);
+    if (e == hipSuccess && wk.up && wk.up->stream != wk.down->stream) e = hipStreamSynchronize(wk.up->stream);
+    if (wk.timing) {
+        wk.fwd_ms = wk.bwd_ms = 0; wk.nf = wk.nb = 0;
+        for (size_t i = 0; i < ops.size(); ++i) {
+            float ms = 0.f;
+            if (!rc && e == hipSuccess && hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) == hipSuccess) {
+                if (ops[i].kind == 0) { wk.fwd_ms += ms; ++wk.nf; } else { wk.bwd_ms += ms; ++wk.nb; }
+            }
+            (void)hipEventDestroy(ev[2 * i]);
+            (void)hipEventDestroy(ev[2 * i + 1]);
+        }
+    }
+    if (rc) return rc;
+    if (e != hipSuccess) return fail(CHIMERA_EDEVICE, "worker replay: %s", hipGetErrorString(e));
+    return CHIMERA_OK;
+}
+
+int chimera_run_worker(int rank, int D, int N) { return chimera_run_worker_algo(CHIMERA_DIRECT, rank, D, N); }
+
+int chimera_worker_last_timing(double* h_fwd_ms, double* h_bwd_ms, int* h_nf, int* h_nb) {
+    if (h_fwd_ms) *h_fwd_ms = g_worker.fwd_ms;
+    if (h_bwd_ms) *h_bwd_ms = g_worker.bwd_ms;
+    if (h_nf) *h_nf = g_worker.nf;
+    if (h_nb) *h_nb = g_worker.nb;
+    return CHIMERA_OK;
+}
+
+// ------------------------------------------------------------ single operators
+int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int n, int k, const void* d_a, int lda,
+                    int a_kc, const void* d_b, int ldb, int b_kc, const void* d_bias, const void* d_r, void* d_c,
+                    void* d_c2, void* hip_stream) {
+    if (!d_a || !d_b || !d_c) return fail(CHIMERA_EINVAL, "NULL operand");
+    if (m < 1 || n < 1 || k < 1) return fail(CHIMERA_EINVAL, "gemm sizes must be positive");
+    if ((k % 8) || (n % 8) || (lda % 8) || (ldb % 8)) return fail(CHIMERA_EINVAL, "k, n, lda, ldb must be multiples of 8");
+    if (!a_kc && (m % 8)) return fail(CHIMERA_EINVAL, "m must be a multiple of 8 when A is stored [k, m]");
+    if (lda < (a_kc ? k : m) || ldb < (b_kc ? k : n)) return fail(CHIMERA_EINVAL, "leading dimension too small");
+    if (epilogue < EPI_NONE || epilogue > EPI_ACCUM_F32) return fail(CHIMERA_EINVAL, "unknown epilogue %d", epilogue);
+    if ((epilogue == EPI_BIAS || epilogue == EPI_BIAS_GELU || epilogue == EPI_BIAS_RESIDUAL) && !d_bias)
+        return fail(CHIMERA_EINVAL, "epilogue %d needs a bias", epilogue);
+    if ((epilogue == EPI_BIAS_RESIDUAL || epilogue == EPI_DGELU) && !d_r) return fail(CHIMERA_EINVAL, "epilogue %d needs R", epilogue);
+    if (epilogue == EPI_BIAS_GELU && !d_c2) return fail(CHIMERA_EINVAL, "epilogue %d needs C2", epilogue);
+    GemmArgs g{};
+    g.m = m; g.n = n; g.k = k; g.a = d_a; g.lda = lda; g.a_kc = a_kc ? 1 : 0; g.b = d_b; g.ldb = ldb; g.b_kc = b_kc ? 1 : 0;
+    g.bias = d_bias; g.r = d_r; g.c = d_c; g.c2 = d_c2; g.epilogue = epilogue; g.gelu_erf = gelu_kind ? 1 : 0;
+    if (impl == 0 && dtype == CHIMERA_BF16 && gemm_mfma_supports(g)) return gemm_mfma_bf16(g, hip_stream);
+    return gemm_reference(dtype, g, hip_stream);
+}
+
+int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x, const void* d_gamma, const void* d_beta,
+                             void* d_y, float* d_mean, float* d_rstd, void* hip_stream) {
+    if (!d_x || !d_gamma || !d_beta || !d_y || !d_mean || !d_rstd) return fail(CHIMERA_EINVAL, "NULL operand");
+    return layernorm_fwd(dtype, rows, cols, d_x, d_gamma, d_beta, d_y, d_mean, d_rstd, hip_stream);
+}
+
+size_t chimera_op_layernorm_bwd_scratch_floats(int rows, int cols) { return layernorm_bwd_scratch_floats(rows, cols); }
+
+int chimera_op_layernorm_bwd(int dtype, int rows, int cols, const void* d_dy, const void* d_x, const float* d_mean,
+                             const float* d_rstd, const void* d_gamma, const void* d_res, void* d_dx, float* d_dgamma,
+                             float* d_dbeta, float* d_scratch, void* hip_stream) {
+    if (!d_dy || !d_x || !d_mean || !d_rstd || !d_gamma || !d_res || !d_dx || !d_dgamma || !d_dbeta || !d_scratch)
+        return fail(CHIMERA_EINVAL, "NULL operand");
+    return layernorm_bwd(dtype, rows, cols, d_dy, d_x, d_mean, d_rstd, d_gamma, d_res, d_dx, d_dgamma, d_dbeta, d_scratch, hip_stream);
+}
+
+size_t chimera_op_colsum_scratch_floats(int rows, int cols) { return colsum_scratch_floats(rows, cols); }
+
+int chimera_op_colsum(int dtype, int rows, int cols, const void* d_x, float* d_out, float* d_scratch, void* hip_stream) {
+    if (!d_x || !d_out || !d_scratch) return fail(CHIMERA_EINVAL, "NULL operand");
+    return colsum(dtype, rows, cols, d_x, d_out, d_scratch, hip_stream);
+}
+
+int chimera_op_attention_fwd(int dtype, int impl, int batch, int seq, int heads, int head_dim, int causal,
+                             const void* d_qkv, void* d_ctx, float* d_lse, void* hip_stream) {
+    if (!d_qkv || !d_ctx || !d_lse) return fail(CHIMERA_EINVAL, "NULL operand");
+    AttnArgs a{};
+    a.batch = batch; a.seq = seq; a.heads = heads; a.head_dim = head_dim; a.causal = causal ? 1 : 0;
+    a.qkv = d_qkv; a.ctx = d_ctx; a.lse = d_lse;
+    if (impl == 0 && dtype == CHIMERA_BF16 && attention_mfma_supports(a)) return attention_fwd_mfma(a, hip_stream);
+    return attention_fwd_reference(dtype, a, hip_stream);
+}
+
+int chimera_op_attention_bwd(int dtype, int impl, int batch, int seq, int heads, int head_dim, int causal,
+                             const void* d_qkv, const void* d_ctx, const float* d_lse, const void* d_dctx, void* d_dqkv,
+                             float* d_delta, void* hip_stream) {
+    if (!d_qkv || !d_ctx || !d_lse || !d_dctx || !d_dqkv || !d_delta) return fail(CHIMERA_EINVAL, "NULL operand");
+    AttnArgs a{};
+    a.batch = batch; a.seq = seq; a.heads = heads; a.head_dim = head_dim; a.causal = causal ? 1 : 0;
+    a.qkv = d_qkv; a.ctx = (void*)d_ctx; a.lse = (float*)d_lse; a.dctx = d_dctx; a.dqkv = d_dqkv; a.delta = d_delta;
+    if (impl == 0 && dtype == CHIMERA_BF16 && attention_mfma_supports(a)) return attention_bwd_mfma(a, hip_stream);
+    return attention_bwd_reference(dtype, a, hip_stream);
+}
+
+}  // extern "C"

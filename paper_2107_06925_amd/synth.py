@@ -86,6 +86,12 @@ def _finish(a, dtype):
     return round_to_bf16(a) if dtype == "bf16" else a
 
 
+def qk_gain_for(hidden, score_std=2.0):
+    """Gain on the Q and K weights that gives attention scores of about this
+    standard deviation (q, k ~ N(0, gain^2 0.02^2 hidden), score = q.k / sqrt(d))."""
+    return float(np.sqrt(score_std / (0.02 * 0.02 * hidden)))
+
+
 def make_stage_params(hidden, layers, stage_id, seed=0, dtype="f32", qk_gain=1.0):
     """Weights of one pipeline stage: list (per block) of dicts keyed by PARAM_ORDER."""
     shapes = param_shapes(hidden)

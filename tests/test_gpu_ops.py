@@ -1,0 +1,160 @@
+"""GPU parity of the single operators against the numpy oracle (through the C ABI)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import block_oracle as bo
+from paper_2107_06925_amd import binding as b
+from paper_2107_06925_amd import synth
+from gpu_util import TOL, assert_close, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+DTYPES = [b.F32, b.BF16]
+IMPLS = [0, 1]
+
+
+def _rand(shape, seed, dtype, scale=1.0):
+    a = np.random.default_rng(seed).standard_normal(shape).astype(np.float32) * scale
+    return synth.round_to_bf16(a) if dtype == b.BF16 else a
+
+
+GEMM_SHAPES = [(128, 384, 128), (200, 136, 72), (512, 512, 256), (304, 1600, 320), (1024, 264, 1032), (8, 8, 8)]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("impl", IMPLS)
+@pytest.mark.parametrize("m,n,k", GEMM_SHAPES)
+@pytest.mark.parametrize("layout", ["fwd", "dgrad", "wgrad"])
+def test_gemm_layouts(dtype, impl, m, n, k, layout):
+    import torch
+    print("gemm", dtype, impl, m, n, k, layout, flush=True)
+    a_kc, b_kc = {"fwd": (1, 0), "dgrad": (1, 1), "wgrad": (0, 0)}[layout]
+    A = _rand((m, k), 1, dtype)
+    B = _rand((k, n), 2, dtype)
+    a_store = A if a_kc else np.ascontiguousarray(A.T)
+    b_store = np.ascontiguousarray(B.T) if b_kc else B
+    want = A.astype(np.float64) @ B.astype(np.float64)
+    da, db = to_dev(a_store, dtype), to_dev(b_store, dtype)
+    if layout == "wgrad":
+        c0 = np.random.default_rng(3).standard_normal((m, n)).astype(np.float32)
+        dc = torch.from_numpy(c0.copy()).cuda()
+        b.chimera_op_gemm(da, db, dc, m, n, k, a_kc, b_kc, b.EPI_ACCUM_F32, impl=impl)
+        b.chimera_op_gemm(da, db, dc, m, n, k, a_kc, b_kc, b.EPI_ACCUM_F32, impl=impl)
+        torch.cuda.synchronize()
+        assert_close(to_np(dc) - c0, 2 * want, dtype, "accumulated twice")
+    else:
+        dc = torch.empty((m, n), dtype=da.dtype, device="cuda")
+        b.chimera_op_gemm(da, db, dc, m, n, k, a_kc, b_kc, b.EPI_NONE, impl=impl)
+        torch.cuda.synchronize()
+        assert_close(to_np(dc), want, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("impl", IMPLS)
+@pytest.mark.parametrize("gelu_erf", [False, True])
+def test_gemm_epilogues(dtype, impl, gelu_erf):
+    import torch
+    m, n, k = 264, 520, 136
+    kind = "erf" if gelu_erf else "tanh"
+    A, B = _rand((m, k), 1, dtype), _rand((k, n), 2, dtype, 0.2)
+    bias, R = _rand((n,), 3, dtype), _rand((m, n), 4, dtype)
+    acc = A.astype(np.float64) @ B.astype(np.float64)
+    da, db, dbias, dr = to_dev(A, dtype), to_dev(B, dtype), to_dev(bias, dtype), to_dev(R, dtype)
+    c = torch.empty((m, n), dtype=da.dtype, device="cuda")
+    c2 = torch.empty_like(c)
+    b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_BIAS, bias=dbias, impl=impl)
+    assert_close(to_np(c), acc + bias, dtype, "bias")
+    b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_BIAS_GELU, bias=dbias, c2=c2, impl=impl, gelu_erf=gelu_erf)
+    assert_close(to_np(c), acc + bias, dtype, "bias+gelu: u")
+    assert_close(to_np(c2), bo.gelu_fwd(acc + bias, kind), dtype, "bias+gelu: g")
+    b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_BIAS_RESIDUAL, bias=dbias, r=dr, impl=impl)
+    assert_close(to_np(c), acc + bias + R, dtype, "bias+residual")
+    b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_DGELU, r=dr, impl=impl, gelu_erf=gelu_erf)
+    assert_close(to_np(c), acc * bo.gelu_grad(R.astype(np.float64), kind), dtype, "dgelu")
+
+
+def test_gemm_argument_errors():
+    import torch
+    a = torch.zeros((16, 16), device="cuda")
+    with pytest.raises(b.ChimeraError):
+        b.chimera_op_gemm(a, a, a, 16, 12, 16, 1, 0)           # n not a multiple of 8
+    with pytest.raises(b.ChimeraError):
+        b.chimera_op_gemm(a, a, a, 16, 16, 16, 1, 0, b.EPI_BIAS)  # bias missing
+    with pytest.raises(b.ChimeraError):
+        b.chimera_op_gemm(a, a, a, 0, 16, 16, 1, 0)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("rows,cols", [(128, 128), (37, 1600), (515, 1024), (64, 2048), (5, 8)])
+def test_layernorm(dtype, rows, cols):
+    import torch
+    print("layernorm", dtype, rows, cols, flush=True)
+    x = _rand((rows, cols), 1, dtype, 2.0) + (0.5 if dtype == b.F32 else 0.0)
+    x = synth.round_to_bf16(x) if dtype == b.BF16 else x
+    g, be = _rand((cols,), 2, dtype), _rand((cols,), 3, dtype)
+    dy, res = _rand((rows, cols), 4, dtype), _rand((rows, cols), 5, dtype)
+    y64, cache = bo.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), be.astype(np.float64))
+    dx64, dg64, db64 = bo.layernorm_bwd(dy.astype(np.float64), cache, g.astype(np.float64))
+    dxd = to_dev(x, dtype)
+    y = torch.empty_like(dxd)
+    mean = torch.empty(rows, device="cuda")
+    rstd = torch.empty(rows, device="cuda")
+    b.chimera_op_layernorm_fwd(dxd, to_dev(g, dtype), to_dev(be, dtype), y, mean, rstd)
+    assert_close(to_np(y), y64, dtype, "y")
+    assert_close(to_np(mean), x.astype(np.float64).mean(-1), b.F32, "mean")
+    assert_close(to_np(rstd), cache[1][:, 0], b.F32, "rstd")
+    dx = torch.empty_like(dxd)
+    dgam = torch.full((cols,), 1.0, device="cuda")
+    dbet = torch.full((cols,), -2.0, device="cuda")
+    b.chimera_op_layernorm_bwd(to_dev(dy, dtype), dxd, mean, rstd, to_dev(g, dtype), to_dev(res, dtype), dx, dgam, dbet)
+    assert_close(to_np(dx), res + dx64, dtype, "dx")
+    assert_close(to_np(dgam) - 1.0, dg64, dtype, "dgamma")
+    assert_close(to_np(dbet) + 2.0, db64, dtype, "dbeta")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("rows,cols", [(128, 384), (1000, 1600), (70, 8), (4096, 4096)])
+def test_colsum(dtype, rows, cols):
+    import torch
+    x = _rand((rows, cols), 1, dtype)
+    out = torch.full((cols,), 3.0, device="cuda")
+    b.chimera_op_colsum(to_dev(x, dtype), out)
+    assert_close(to_np(out) - 3.0, x.astype(np.float64).sum(0), b.F32, "colsum", scale=10.0)
+
+
+ATTN_SHAPES = [(2, 64, 4, 32), (1, 100, 2, 64), (2, 256, 3, 64), (1, 192, 2, 128), (3, 1, 2, 64), (1, 77, 1, 16)]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("impl", IMPLS)
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("batch,seq,heads,d", ATTN_SHAPES)
+def test_attention(dtype, impl, causal, batch, seq, heads, d):
+    import torch
+    print("attention", dtype, impl, causal, batch, seq, heads, d, flush=True)
+    H = heads * d
+    qkv = _rand((batch * seq, 3 * H), 1, dtype, 1.5)       # peaked softmax: scores ~ N(0, 2.25 d)/sqrt(d)
+    dctx = _rand((batch * seq, H), 2, dtype)
+    ctx64, probs = bo.attention_fwd(qkv.astype(np.float64), batch, seq, heads, causal)
+    dqkv64 = bo.attention_bwd(dctx.astype(np.float64), qkv.astype(np.float64), probs, batch, seq, heads)
+    dq = to_dev(qkv, dtype)
+    ctx = torch.empty((batch * seq, H), dtype=dq.dtype, device="cuda")
+    lse = torch.empty((batch, heads, seq), device="cuda")
+    b.chimera_op_attention_fwd(dq, ctx, lse, batch, seq, heads, d, causal, impl=impl)
+    assert_close(to_np(ctx), ctx64, dtype, "ctx")
+    # lse: log-sum-exp of the scaled, masked scores
+    q = qkv.astype(np.float64)
+    bb, hh = batch - 1, heads - 1
+    s = q[bb * seq:(bb + 1) * seq, hh * d:(hh + 1) * d] @ q[bb * seq:(bb + 1) * seq, H + hh * d:H + (hh + 1) * d].T / math.sqrt(d)
+    if causal:
+        s = np.where(np.tril(np.ones((seq, seq), dtype=bool)), s, -np.inf)
+    want_lse = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
+    assert np.max(np.abs(to_np(lse)[bb, hh] - want_lse)) < (1e-4 if dtype == b.F32 else 2e-2)
+    dqkv = torch.empty_like(dq)
+    delta = torch.empty((batch, heads, seq), device="cuda")
+    # the backward reads the forward's own ctx and lse, as the stage does
+    b.chimera_op_attention_bwd(dq, ctx, lse, to_dev(dctx, dtype), dqkv, delta, batch, seq, heads, d, causal, impl=impl)
+    got = to_np(dqkv)
+    for name, lo in (("dq", 0), ("dk", H), ("dv", 2 * H)):
+        assert_close(got[:, lo:lo + H], dqkv64[:, lo:lo + H], dtype, name)
