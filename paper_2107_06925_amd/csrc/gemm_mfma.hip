@@ -1,5 +1,308 @@
+// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), float
+// accumulation, for the three products of a linear layer:
+//   forward  Y  = X W      A k-contiguous, B stored [k, n]
+//   dgrad    dX = dY W^T   A k-contiguous, B k-contiguous
+//   wgrad    dW += X^T dY  A stored [k, m], B stored [k, n]  (k = tokens)
+//
+// One workgroup of 4 or 8 wavefronts computes a BM x BN tile; each wavefront
+// owns a 128x64 or 64x64 part of it as a grid of 32x32 MFMA tiles whose
+// accumulators never leave the registers.  The k loop moves BK = 64 at a time
+// through LDS with two buffers: while the matrix cores work on buffer b, the
+// loads of the next k step are already in flight to registers and are written
+// to buffer b^1 afterwards, one barrier per step.
+//
+// LDS always holds both operands as [row][k] with k contiguous (128 bytes per
+// row = 8 chunks of 16 bytes), which is the order the MFMA operand registers
+// want: lane l of a wavefront feeds row l%32 with the 8 consecutive k values
+// of chunk 2*kk + l/32.  An operand that is k-contiguous in memory is copied
+// chunk by chunk.  An operand whose OTHER index is contiguous in memory (W in
+// the forward, both operands in wgrad) is read in coalesced 16-byte pieces
+// along that index for 8 (or 4) consecutive k, transposed inside the thread's
+// registers, and written as k-contiguous pieces, so no transposed copy of any
+// activation or weight ever exists in HBM.
+// Chunk c of row r is stored at position c ^ (r & 7) ^ ((r >> 3) & 7): rows
+// r..r+7 of one logical chunk (an MFMA operand read) and rows r, r+8, ...,
+// r+56 (a transposed write) both fall on 8 different bank groups.
+//
+// Workgroups are renumbered so that each of the 8 XCDs (own L2 each; the
+// hardware deals consecutive workgroup ids round-robin over them) works on a
+// contiguous range of tiles, and tiles are walked in groups of 8 tile rows so
+// that the tiles in flight on one XCD share operand panels in its L2.
 #include "device.h"
+
+#include <cstdlib>
+#include <cstring>
+
 namespace chimera {
-bool gemm_mfma_supports(const GemmArgs&) { return false; }
-int gemm_mfma_bf16(const GemmArgs&, void*) { return fail(CHIMERA_EINVAL, "matrix-core gemm not built"); }
+
+namespace {
+
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;
+constexpr int GROUP_M = 8;       // tile rows per raster group
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
+
+__device__ __forceinline__ unsigned half_of(const uint4& q, int t) {
+    const unsigned w = (t >> 1) == 0 ? q.x : (t >> 1) == 1 ? q.y : (t >> 1) == 2 ? q.z : q.w;
+    return (t & 1) ? (w >> 16) : (w & 0xffffu);
 }
+
+// k rows per transposing unit: 8 when every thread then still has a unit, else 4
+template <int ROWS, int NT> struct McShape {
+    static constexpr int KB = (ROWS * BK / 64 >= NT) ? 8 : 4;
+    static constexpr int UPT = ROWS * BK / (8 * KB * NT);   // units per thread
+    static_assert(UPT >= 1, "tile too small for the workgroup");
+};
+template <int ROWS, int NT, bool KC> struct Staged {
+    static constexpr int N = KC ? ROWS * (BK / 8) / NT : McShape<ROWS, NT>::UPT * McShape<ROWS, NT>::KB;
+    uint4 v[N];
+};
+
+// global -> registers for one operand tile of ROWS rows x BK k values.
+// KC: element (row, k) at base[row * ld + k].  !KC: at base[k * ld + row].
+template <int ROWS, int NT, bool KC>
+__device__ __forceinline__ void load_tile(Staged<ROWS, NT, KC>& st, const bf16_t* __restrict__ base, int ld, int row0,
+                                          int nrows, int k0, int K, int tid) {
+    if constexpr (KC) {
+        constexpr int CPT = ROWS * (BK / 8) / NT;
+#pragma unroll
+        for (int it = 0; it < CPT; ++it) {
+            const int c = tid + it * NT;
+            const int gr = row0 + (c >> 3), gk = k0 + (c & 7) * 8;
+            uint4 q = make_uint4(0u, 0u, 0u, 0u);
+            if (gr < nrows && gk < K) q = *reinterpret_cast<const uint4*>(base + (size_t)gr * ld + gk);
+            st.v[it] = q;
+        }
+    } else {
+        constexpr int KB = McShape<ROWS, NT>::KB, UPT = McShape<ROWS, NT>::UPT, IG = ROWS / 8;
+#pragma unroll
+        for (int it = 0; it < UPT; ++it) {
+            const int u = tid + it * NT;
+            const int gi = row0 + (u % IG) * 8, kb = k0 + (u / IG) * KB;
+#pragma unroll
+            for (int r = 0; r < KB; ++r) {
+                uint4 q = make_uint4(0u, 0u, 0u, 0u);
+                if (gi < nrows && kb + r < K) q = *reinterpret_cast<const uint4*>(base + (size_t)(kb + r) * ld + gi);
+                st.v[it * KB + r] = q;
+            }
+        }
+    }
+}
+
+// registers -> LDS tile [ROWS][BK], swizzled.
+template <int ROWS, int NT, bool KC>
+__device__ __forceinline__ void store_tile(const Staged<ROWS, NT, KC>& st, bf16_t* lds, int tid) {
+    if constexpr (KC) {
+        constexpr int CPT = ROWS * (BK / 8) / NT;
+#pragma unroll
+        for (int it = 0; it < CPT; ++it) {
+            const int c = tid + it * NT;
+            const int row = c >> 3, kc = c & 7;
+            *reinterpret_cast<uint4*>(lds + row * BK + swz(row, kc) * 8) = st.v[it];
+        }
+    } else {
+        constexpr int KB = McShape<ROWS, NT>::KB, UPT = McShape<ROWS, NT>::UPT, IG = ROWS / 8;
+#pragma unroll
+        for (int it = 0; it < UPT; ++it) {
+            const int u = tid + it * NT;
+            const int ig = u % IG, kg = u / IG;
+            const int chunk = (kg * KB) >> 3, within = (kg * KB) & 7;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int row = ig * 8 + t;
+                bf16_t* dst = lds + row * BK + swz(row, chunk) * 8 + within;
+                unsigned w[KB / 2];
+#pragma unroll
+                for (int p = 0; p < KB / 2; ++p)
+                    w[p] = half_of(st.v[it * KB + 2 * p], t) | (half_of(st.v[it * KB + 2 * p + 1], t) << 16);
+                if constexpr (KB == 8) *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+                else *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+            }
+        }
+    }
+}
+
+// Epilogue of one wavefront.  Accumulator register r of lane l holds
+// C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
+template <int EPI, int TM, int TN>
+__device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], int row_base, int col_base, int m, int n,
+                                         const bf16_t* __restrict__ bias, const bf16_t* __restrict__ R,
+                                         void* __restrict__ c, bf16_t* __restrict__ C2, int erf_form, int lane) {
+    bf16_t* C = (bf16_t*)c;
+    float* Cf = (float*)c;
+    const int l32 = lane & 31, lhi = lane >> 5;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int col = col_base + b * 32 + l32;
+        if (col >= n) continue;
+        float bv = 0.f;
+        if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RESIDUAL) bv = (float)bias[col];
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row_base + a * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+                if (row >= m) continue;
+                const size_t idx = (size_t)row * n + col;
+                const float v = acc[a][b][r];
+                if constexpr (EPI == EPI_NONE) C[idx] = (bf16_t)v;
+                else if constexpr (EPI == EPI_BIAS) C[idx] = (bf16_t)(v + bv);
+                else if constexpr (EPI == EPI_BIAS_GELU) {
+                    const float u = v + bv;
+                    C[idx] = (bf16_t)u;
+                    C2[idx] = (bf16_t)gelu_f(u, erf_form);
+                } else if constexpr (EPI == EPI_BIAS_RESIDUAL) C[idx] = (bf16_t)(v + bv + (float)R[idx]);
+                else if constexpr (EPI == EPI_DGELU) C[idx] = (bf16_t)(v * gelu_grad_f((float)R[idx], erf_form));
+                else Cf[idx] += v;
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
+    const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
+    int ldb, int epi, int erf_form, int tiles_m, int tiles_n) {
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN;    // wavefront tile
+    constexpr int TM = WM / 32, TN = WN / 32;      // MFMA tiles per wavefront
+    __shared__ __attribute__((aligned(16))) bf16_t lds[2][(BM + BN) * BK];
+
+    // workgroup id -> tile, XCD-contiguous then grouped raster
+    const int nblk = tiles_m * tiles_n;
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int pid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
+    const int width = GROUP_M * tiles_n;
+    const int first_m = (pid / width) * GROUP_M;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int tile_m = first_m + (pid % width) % gsz;
+    const int tile_n = (pid % width) / gsz;
+    const int i0 = tile_m * BM, j0 = tile_n * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    Staged<BM, NT, A_KC> ra;
+    Staged<BN, NT, B_KC> rb;
+    load_tile<BM, NT, A_KC>(ra, A, lda, i0, m, 0, k, tid);
+    load_tile<BN, NT, B_KC>(rb, B, ldb, j0, n, 0, k, tid);
+    store_tile<BM, NT, A_KC>(ra, lds[0], tid);
+    store_tile<BN, NT, B_KC>(rb, lds[0] + BM * BK, tid);
+    __syncthreads();
+
+    const int KT = (k + BK - 1) / BK;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT) {
+            load_tile<BM, NT, A_KC>(ra, A, lda, i0, m, (kt + 1) * BK, k, tid);
+            load_tile<BN, NT, B_KC>(rb, B, ldb, j0, n, (kt + 1) * BK, k, tid);
+        }
+        const bf16_t* As = lds[buf];
+        const bf16_t* Bs = lds[buf] + BM * BK;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const int row = wm0 + a * 32 + l32;
+                af[a] = *reinterpret_cast<const bf16x8*>(As + row * BK + swz(row, kk * 2 + lhi) * 8);
+            }
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const int row = wn0 + b * 32 + l32;
+                bfr[b] = *reinterpret_cast<const bf16x8*>(Bs + row * BK + swz(row, kk * 2 + lhi) * 8);
+            }
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+        }
+        if (kt + 1 < KT) {
+            store_tile<BM, NT, A_KC>(ra, lds[buf ^ 1], tid);
+            store_tile<BN, NT, B_KC>(rb, lds[buf ^ 1] + BM * BK, tid);
+        }
+        __syncthreads();
+    }
+
+    const int rb0 = i0 + wm0, cb0 = j0 + wn0;
+    switch (epi) {
+        case EPI_NONE: epilogue<EPI_NONE, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
+        case EPI_BIAS: epilogue<EPI_BIAS, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
+        case EPI_BIAS_GELU: epilogue<EPI_BIAS_GELU, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
+        case EPI_BIAS_RESIDUAL: epilogue<EPI_BIAS_RESIDUAL, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
+        case EPI_DGELU: epilogue<EPI_DGELU, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
+        default: epilogue<EPI_ACCUM_F32, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
+    }
+}
+
+struct TileChoice { int bm, bn; };
+
+TileChoice forced_tile() {
+    TileChoice c{0, 0};
+    const char* e = std::getenv("CHIMERA_GEMM_TILE");   // e.g. "256x128"; tuning aid
+    if (e) std::sscanf(e, "%dx%d", &c.bm, &c.bn);
+    return c;
+}
+
+// 256x256 (8 wavefronts) once it gives most of the 256 CUs a tile, else 128x128
+// (4 wavefronts, two workgroups per CU).  Thresholds from measurements on MI355X.
+TileChoice choose_tile(const GemmArgs& g) {
+    const TileChoice f = forced_tile();
+    if (f.bm) return f;
+    const long t256 = (long)((g.m + 255) / 256) * ((g.n + 255) / 256);
+    if (t256 >= 160) return {256, 256};
+    return {128, 128};
+}
+
+template <int BM, int BN, int WGM, int WGN>
+int launch_layout(const GemmArgs& g, hipStream_t s) {
+    const int tm = (g.m + BM - 1) / BM, tn = (g.n + BN - 1) / BN;
+    const dim3 grid(tm * tn), block(WGM * WGN * 64);
+#define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                              \
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, AKC, BKC>), grid, block, 0, s, (const bf16_t*)g.a,      \
+                       (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c, (bf16_t*)g.c2, g.m, g.n, \
+                       g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf, tm, tn)
+    if (g.a_kc && !g.b_kc) CHIMERA_GEMM_LAUNCH(true, false);
+    else if (g.a_kc && g.b_kc) CHIMERA_GEMM_LAUNCH(true, true);
+    else CHIMERA_GEMM_LAUNCH(false, false);
+#undef CHIMERA_GEMM_LAUNCH
+    CHIMERA_LAUNCH_CHECK("bf16 gemm");
+    return CHIMERA_OK;
+}
+
+}  // namespace
+
+bool gemm_mfma_supports(const GemmArgs& g) {
+    if (!g.a_kc && g.b_kc) return false;                       // layout no linear layer needs
+    if ((g.k % 8) || (g.n % 8) || (g.lda % 8) || (g.ldb % 8)) return false;
+    if (!g.a_kc && (g.m % 8)) return false;
+    if (((uintptr_t)g.a | (uintptr_t)g.b) & 15) return false;  // 16-byte vector loads
+    return g.m >= 1 && g.n >= 1 && g.k >= 1;
+}
+
+int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
+    if (!gemm_mfma_supports(g)) return fail(CHIMERA_EINVAL, "bf16 matrix-core gemm: unsupported shape or layout");
+    if (g.epilogue < EPI_NONE || g.epilogue > EPI_ACCUM_F32) return fail(CHIMERA_EINVAL, "unknown epilogue %d", g.epilogue);
+    hipStream_t s = (hipStream_t)stream;
+    const TileChoice t = choose_tile(g);
+    if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4>(g, s);
+    if (t.bm == 256 && t.bn == 128) return launch_layout<256, 128, 2, 2>(g, s);
+    if (t.bm == 128 && t.bn == 128) return launch_layout<128, 128, 2, 2>(g, s);
+    return fail(CHIMERA_EINVAL, "no %dx%d gemm tile", t.bm, t.bn);
+}
+
+}  // namespace chimera
