@@ -179,6 +179,18 @@ int chimera_worker_set_timing(int on);
  * backward ops (HIP events around every op), and the op counts. */
 int chimera_worker_last_timing(double* h_fwd_ms, double* h_bwd_ms, int* h_nf, int* h_nb);
 
+/* Per-kernel-class timing of everything the stages launch while enabled: a HIP
+ * event pair brackets every launch (this slows the replay a little, so keep it
+ * off when timing whole iterations).  Classes: 0 GEMM forward, 1 GEMM dgrad,
+ * 2 GEMM wgrad, 3 attention forward, 4 attention backward, 5 LayerNorm forward,
+ * 6 LayerNorm backward, 7 column sums.  chimera_profile_read must be called
+ * with the stream idle; it returns the summed milliseconds, the number of
+ * launches and the summed algorithmic work (flop for classes 0-4, bytes for
+ * 5-7) since the last chimera_profile_reset. */
+int chimera_profile_enable(int on);
+int chimera_profile_reset(void);
+int chimera_profile_read(int cls, double* h_ms, long long* h_launches, double* h_work);
+
 /* ---------------------------------------------------------- single operators
  * The kernels a stage is made of, callable on raw device buffers so that each
  * can be checked and profiled alone.  dtype as above; `impl` 0 = the kernel

@@ -54,6 +54,9 @@ _SIGNATURES = {
     "chimera_run_worker_algo": (_i, [_i, _i, _i, _i]),
     "chimera_worker_set_timing": (_i, [_i]),
     "chimera_worker_last_timing": (_i, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i), C.POINTER(_i)]),
+    "chimera_profile_enable": (_i, [_i]),
+    "chimera_profile_reset": (_i, []),
+    "chimera_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_bwd_scratch_floats": (_sz, [_i, _i]),
@@ -206,6 +209,27 @@ def chimera_worker_last_timing():
     f, b, nf, nb = C.c_double(), C.c_double(), C.c_int(), C.c_int()
     check(lib().chimera_worker_last_timing(C.byref(f), C.byref(b), C.byref(nf), C.byref(nb)))
     return dict(fwd_ms=f.value, bwd_ms=b.value, n_fwd=nf.value, n_bwd=nb.value)
+
+
+PROFILE_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum")
+
+
+def chimera_profile_enable(on):
+    check(lib().chimera_profile_enable(int(on)))
+
+
+def chimera_profile_reset():
+    check(lib().chimera_profile_reset())
+
+
+def chimera_profile_read():
+    """{class name: dict(ms, launches, work)}; work is flop (gemm, attention) or bytes."""
+    out = {}
+    for i, name in enumerate(PROFILE_CLASSES):
+        ms, n, w = C.c_double(), C.c_longlong(), C.c_double()
+        check(lib().chimera_profile_read(i, C.byref(ms), C.byref(n), C.byref(w)))
+        out[name] = dict(ms=ms.value, launches=n.value, work=w.value)
+    return out
 
 
 def stash_slots_needed(algo, D, N, rank):

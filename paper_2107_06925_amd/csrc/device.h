@@ -52,6 +52,18 @@ template <> __device__ __forceinline__ void store_vec<bf16_t>(bf16_t* p, const f
     *reinterpret_cast<bf16x8*>(p) = v;
 }
 
+// V consecutive elements of type T (V = 4 or 8), widened to float / narrowed from float.
+template <typename T, int V> __device__ __forceinline__ void load_elems(const T* p, float* out) {
+    constexpr int PER = Elem<T>::VEC;
+#pragma unroll
+    for (int i = 0; i < V; i += PER) load_vec<T>(p + i, out + i);
+}
+template <typename T, int V> __device__ __forceinline__ void store_elems(T* p, const float* in) {
+    constexpr int PER = Elem<T>::VEC;
+#pragma unroll
+    for (int i = 0; i < V; i += PER) store_vec<T>(p + i, in + i);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);

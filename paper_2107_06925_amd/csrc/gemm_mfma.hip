@@ -127,7 +127,7 @@ __device__ __forceinline__ void store_tile(const Staged<ROWS, NT, KC>& st, bf16_
 
 // Epilogue of one wavefront.  Accumulator register r of lane l holds
 // C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
-template <int EPI, int TM, int TN>
+template <int EPI, bool RF32, bool CF32, int TM, int TN>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], int row_base, int col_base, int m, int n,
                                          const bf16_t* __restrict__ bias, const bf16_t* __restrict__ R,
                                          void* __restrict__ c, bf16_t* __restrict__ C2, int erf_form, int lane) {
@@ -154,7 +154,11 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], int row_ba
                     const float u = v + bv;
                     C[idx] = (bf16_t)u;
                     C2[idx] = (bf16_t)gelu_f(u, erf_form);
-                } else if constexpr (EPI == EPI_BIAS_RESIDUAL) C[idx] = (bf16_t)(v + bv + (float)R[idx]);
+                } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
+                    const float rv = RF32 ? reinterpret_cast<const float*>(R)[idx] : (float)R[idx];
+                    if constexpr (CF32) Cf[idx] = v + bv + rv;
+                    else C[idx] = (bf16_t)(v + bv + rv);
+                }
                 else if constexpr (EPI == EPI_DGELU) C[idx] = (bf16_t)(v * gelu_grad_f((float)R[idx], erf_form));
                 else Cf[idx] += v;
             }
@@ -162,11 +166,11 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], int row_ba
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
+template <int BM, int BN, int WGM, int WGN, int PF, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(BM * BN <= 128 * 128 ? 2 : 1, 2))) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int erf_form, int tiles_m, int tiles_n) {
+    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;    // wavefront tile
     constexpr int TM = WM / 32, TN = WN / 32;      // MFMA tiles per wavefront
@@ -195,21 +199,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    Staged<BM, NT, A_KC> ra;
-    Staged<BN, NT, B_KC> rb;
-    load_tile<BM, NT, A_KC>(ra, A, lda, i0, m, 0, k, tid);
-    load_tile<BN, NT, B_KC>(rb, B, ldb, j0, n, 0, k, tid);
-    store_tile<BM, NT, A_KC>(ra, lds[0], tid);
-    store_tile<BN, NT, B_KC>(rb, lds[0] + BM * BK, tid);
-    __syncthreads();
-
-    const int KT = (k + BK - 1) / BK;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) {
-            load_tile<BM, NT, A_KC>(ra, A, lda, i0, m, (kt + 1) * BK, k, tid);
-            load_tile<BN, NT, B_KC>(rb, B, ldb, j0, n, (kt + 1) * BK, k, tid);
-        }
+    // one k step of MFMA work out of LDS buffer `buf`
+    auto compute = [&](int buf) {
         const bf16_t* As = lds[buf];
         const bf16_t* Bs = lds[buf] + BM * BK;
 #pragma unroll
@@ -231,22 +222,68 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
                 for (int b = 0; b < TN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
         }
-        if (kt + 1 < KT) {
-            store_tile<BM, NT, A_KC>(ra, lds[buf ^ 1], tid);
-            store_tile<BN, NT, B_KC>(rb, lds[buf ^ 1] + BM * BK, tid);
-        }
+    };
+    auto fetch = [&](Staged<BM, NT, A_KC>& ra, Staged<BN, NT, B_KC>& rb, int kt) {
+        load_tile<BM, NT, A_KC>(ra, A, lda, i0, m, kt * BK, k, tid);
+        load_tile<BN, NT, B_KC>(rb, B, ldb, j0, n, kt * BK, k, tid);
+    };
+    auto stash = [&](const Staged<BM, NT, A_KC>& ra, const Staged<BN, NT, B_KC>& rb, int buf) {
+        store_tile<BM, NT, A_KC>(ra, lds[buf], tid);
+        store_tile<BN, NT, B_KC>(rb, lds[buf] + BM * BK, tid);
+    };
+
+    const int KT = (k + BK - 1) / BK;
+    if constexpr (PF == 1) {
+        // global loads run one k step ahead of the matrix cores
+        Staged<BM, NT, A_KC> ra;
+        Staged<BN, NT, B_KC> rb;
+        fetch(ra, rb, 0);
+        stash(ra, rb, 0);
         __syncthreads();
+        for (int kt = 0; kt < KT; ++kt) {
+            const int buf = kt & 1;
+            if (kt + 1 < KT) fetch(ra, rb, kt + 1);
+            compute(buf);
+            if (kt + 1 < KT) stash(ra, rb, buf ^ 1);
+            __syncthreads();
+        }
+    } else {
+        // global loads run two k steps ahead (two register sets), LDS one step ahead
+        Staged<BM, NT, A_KC> ra0, ra1;
+        Staged<BN, NT, B_KC> rb0, rb1;
+        fetch(ra0, rb0, 0);
+        if (KT > 1) fetch(ra1, rb1, 1);
+        stash(ra0, rb0, 0);
+        __syncthreads();
+        for (int kt = 0; kt < KT; kt += 2) {
+            if (kt + 2 < KT) fetch(ra0, rb0, kt + 2);
+            compute(0);
+            if (kt + 1 < KT) stash(ra1, rb1, 1);
+            __syncthreads();
+            if (kt + 1 >= KT) break;
+            if (kt + 3 < KT) fetch(ra1, rb1, kt + 3);
+            compute(1);
+            if (kt + 2 < KT) stash(ra0, rb0, 0);
+            __syncthreads();
+        }
     }
 
     const int rb0 = i0 + wm0, cb0 = j0 + wn0;
+#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
     switch (epi) {
-        case EPI_NONE: epilogue<EPI_NONE, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
-        case EPI_BIAS: epilogue<EPI_BIAS, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
-        case EPI_BIAS_GELU: epilogue<EPI_BIAS_GELU, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
-        case EPI_BIAS_RESIDUAL: epilogue<EPI_BIAS_RESIDUAL, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
-        case EPI_DGELU: epilogue<EPI_DGELU, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
-        default: epilogue<EPI_ACCUM_F32, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane); break;
+        case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
+        case EPI_BIAS: CHIMERA_EPI(EPI_BIAS, false, false); break;
+        case EPI_BIAS_GELU: CHIMERA_EPI(EPI_BIAS_GELU, false, false); break;
+        case EPI_BIAS_RESIDUAL:                    // res_types: bit 0 = R is float, bit 1 = C is float
+            if (res_types == 0) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, false);
+            else if (res_types == 1) CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, false);
+            else if (res_types == 2) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, true);
+            else CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, true);
+            break;
+        case EPI_DGELU: CHIMERA_EPI(EPI_DGELU, false, false); break;
+        default: CHIMERA_EPI(EPI_ACCUM_F32, false, false); break;
     }
+#undef CHIMERA_EPI
 }
 
 struct TileChoice { int bm, bn; };
@@ -268,14 +305,14 @@ TileChoice choose_tile(const GemmArgs& g) {
     return {128, 128};
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int PF>
 int launch_layout(const GemmArgs& g, hipStream_t s) {
     const int tm = (g.m + BM - 1) / BM, tn = (g.n + BN - 1) / BN;
     const dim3 grid(tm * tn), block(WGM * WGN * 64);
 #define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                              \
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, AKC, BKC>), grid, block, 0, s, (const bf16_t*)g.a,      \
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, PF, AKC, BKC>), grid, block, 0, s, (const bf16_t*)g.a,      \
                        (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c, (bf16_t*)g.c2, g.m, g.n, \
-                       g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf, tm, tn)
+                       g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf, (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn)
     if (g.a_kc && !g.b_kc) CHIMERA_GEMM_LAUNCH(true, false);
     else if (g.a_kc && g.b_kc) CHIMERA_GEMM_LAUNCH(true, true);
     else CHIMERA_GEMM_LAUNCH(false, false);
@@ -299,9 +336,9 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     if (g.epilogue < EPI_NONE || g.epilogue > EPI_ACCUM_F32) return fail(CHIMERA_EINVAL, "unknown epilogue %d", g.epilogue);
     hipStream_t s = (hipStream_t)stream;
     const TileChoice t = choose_tile(g);
-    if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4>(g, s);
-    if (t.bm == 256 && t.bn == 128) return launch_layout<256, 128, 2, 2>(g, s);
-    if (t.bm == 128 && t.bn == 128) return launch_layout<128, 128, 2, 2>(g, s);
+    if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4, 1>(g, s);
+    const char* pf = std::getenv("CHIMERA_GEMM_PF");
+    if (t.bm == 128 && t.bn == 128) return (pf && pf[0] == '2') ? launch_layout<128, 128, 2, 2, 2>(g, s) : launch_layout<128, 128, 2, 2, 1>(g, s);
     return fail(CHIMERA_EINVAL, "no %dx%d gemm tile", t.bm, t.bn);
 }
 

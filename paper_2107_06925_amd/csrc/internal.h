@@ -45,7 +45,8 @@ struct GemmArgs {
     const void* a; int lda; int a_kc;   // a_kc: A stored [m,k]; else [k,m]
     const void* b; int ldb; int b_kc;   // b_kc: B stored [n,k]; else [k,n]
     const void* bias;                   // [n], stage dtype
-    const void* r;                      // [m,n], stage dtype
+    const void* r;                      // [m,n], stage dtype (float if r_f32)
+    int r_f32, c_f32;                   // EPI_BIAS_RESIDUAL on bf16 only: R is / C becomes float
     void* c;                            // [m,n]
     void* c2;                           // [m,n]
     int epilogue;
@@ -56,12 +57,15 @@ int gemm_reference(int dtype, const GemmArgs& g, void* stream);
 int gemm_mfma_bf16(const GemmArgs& g, void* stream);
 bool gemm_mfma_supports(const GemmArgs& g);
 
-int layernorm_fwd(int dtype, int rows, int cols, const void* x, const void* gamma, const void* beta,
+// x_f32 / res_f32: that operand is float although the stage dtype is bf16 (the
+// residual stream inside a bf16 stage is kept in float).  dx_lo (stage dtype) and
+// dx_hi (float) may each be null, not both.
+int layernorm_fwd(int dtype, int rows, int cols, const void* x, int x_f32, const void* gamma, const void* beta,
                   void* y, float* mean, float* rstd, void* stream);
 size_t layernorm_bwd_scratch_floats(int rows, int cols);
-int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, const float* mean,
-                  const float* rstd, const void* gamma, const void* res, void* dx, float* dgamma,
-                  float* dbeta, float* scratch, void* stream);
+int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, int x_f32, const float* mean,
+                  const float* rstd, const void* gamma, const void* res, int res_f32, void* dx_lo, float* dx_hi,
+                  float* dgamma, float* dbeta, float* scratch, void* stream);
 size_t colsum_scratch_floats(int rows, int cols);
 int colsum(int dtype, int rows, int cols, const void* x, float* out, float* scratch, void* stream);
 int fill_zero_f32(float* p, size_t n, void* stream);

@@ -24,9 +24,12 @@ __device__ __forceinline__ void epilogue_scalar(const GemmArgs& g, int row, int 
             ((T*)g.c2)[idx] = Elem<T>::from_f(gelu_f(u, g.gelu_erf));
             break;
         }
-        case EPI_BIAS_RESIDUAL:
-            ((T*)g.c)[idx] = Elem<T>::from_f(acc + Elem<T>::to_f(((const T*)g.bias)[col]) + Elem<T>::to_f(((const T*)g.r)[idx]));
+        case EPI_BIAS_RESIDUAL: {
+            const float rv = g.r_f32 ? ((const float*)g.r)[idx] : Elem<T>::to_f(((const T*)g.r)[idx]);
+            const float v = acc + Elem<T>::to_f(((const T*)g.bias)[col]) + rv;
+            if (g.c_f32) ((float*)g.c)[idx] = v; else ((T*)g.c)[idx] = Elem<T>::from_f(v);
             break;
+        }
         case EPI_DGELU:
             ((T*)g.c)[idx] = Elem<T>::from_f(acc * gelu_grad_f(Elem<T>::to_f(((const T*)g.r)[idx]), g.gelu_erf));
             break;

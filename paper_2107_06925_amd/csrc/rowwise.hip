@@ -17,8 +17,8 @@ constexpr int CS_ROWS = 64;        // rows per block in the column sum
 // ------------------------------------------------------------- LayerNorm fwd
 // y = (x - mean) * rstd * gamma + beta, biased variance, eps 1e-5.
 // T chunks per lane are kept in registers between the passes.
-template <typename T, int MAXT>
-__global__ __launch_bounds__(LN_WAVES* WAVE) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+template <typename TX, typename T, int MAXT>
+__global__ __launch_bounds__(LN_WAVES* WAVE) void ln_fwd_kernel(const TX* __restrict__ x, const T* __restrict__ gamma,
                                                                 const T* __restrict__ beta, T* __restrict__ y,
                                                                 float* __restrict__ mean, float* __restrict__ rstd,
                                                                 int rows, int cols) {
@@ -27,14 +27,14 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_fwd_kernel(const T* __restr
     const int row = blockIdx.x * LN_WAVES + threadIdx.x / WAVE;
     if (row >= rows) return;
     const int nchunk = cols / V;
-    const T* xr = x + (size_t)row * cols;
+    const TX* xr = x + (size_t)row * cols;
     float v[MAXT][V];
     float s = 0.f;
 #pragma unroll
     for (int t = 0; t < MAXT; ++t) {
         const int c = lane + t * WAVE;
         if (c < nchunk) {
-            load_vec<T>(xr + c * V, v[t]);
+            load_elems<TX, V>(xr + c * V, v[t]);
 #pragma unroll
             for (int e = 0; e < V; ++e) s += v[t][e];
         }
@@ -74,13 +74,15 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_fwd_kernel(const T* __restr
 // sums accumulate in registers, are combined over the block's wavefronts in
 // LDS in a fixed order and leave as one partial row per block:
 // partial[block][0][cols] = dgamma part, partial[block][1][cols] = dbeta part.
-template <typename T, int MAXT>
-__global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+// x may be float while dy is bf16 (TX), the residual gradient likewise (TR); dx is
+// written as T (dx_lo, may be null) and/or as float (dx_hi, may be null).
+template <typename TX, typename TR, typename T, int MAXT>
+__global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restrict__ dy, const TX* __restrict__ x,
                                                                 const float* __restrict__ mean,
                                                                 const float* __restrict__ rstd,
-                                                                const T* __restrict__ gamma, const T* __restrict__ res,
-                                                                T* __restrict__ dx, float* __restrict__ partial,
-                                                                int rows, int cols) {
+                                                                const T* __restrict__ gamma, const TR* __restrict__ res,
+                                                                T* __restrict__ dx_lo, float* __restrict__ dx_hi,
+                                                                float* __restrict__ partial, int rows, int cols) {
     constexpr int V = Elem<T>::VEC;
     extern __shared__ float red[];   // [2][cols]
     const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
@@ -94,9 +96,10 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
         if (c < nchunk) load_vec<T>(gamma + c * V, g[t]);
     }
     const int row0 = blockIdx.x * LNB_ROWS;
-    for (int r = wave; r < LNB_ROWS; r += LN_WAVES) {
-        const int row = row0 + r;
-        if (row >= rows) break;
+#pragma unroll
+    for (int rr = 0; rr < LNB_ROWS / LN_WAVES; ++rr) {   // unrolled: the rows of a wavefront are independent
+        const int row = row0 + wave + rr * LN_WAVES;
+        if (row >= rows) continue;
         const float mu = mean[row], rs = rstd[row];
         float dxh[MAXT][V], xh[MAXT][V];
         float s1 = 0.f, s2 = 0.f;
@@ -106,7 +109,7 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
             if (c < nchunk) {
                 float d[V], xv[V];
                 load_vec<T>(dy + (size_t)row * cols + c * V, d);
-                load_vec<T>(x + (size_t)row * cols + c * V, xv);
+                load_elems<TX, V>(x + (size_t)row * cols + c * V, xv);
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     xh[t][e] = (xv[e] - mu) * rs;
@@ -125,10 +128,11 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
             const int c = lane + t * WAVE;
             if (c < nchunk) {
                 float rv[V], o[V];
-                load_vec<T>(res + (size_t)row * cols + c * V, rv);
+                load_elems<TR, V>(res + (size_t)row * cols + c * V, rv);
 #pragma unroll
                 for (int e = 0; e < V; ++e) o[e] = rv[e] + rs * (dxh[t][e] - m1 - xh[t][e] * m2);
-                store_vec<T>(dx + (size_t)row * cols + c * V, o);
+                if (dx_lo) store_vec<T>(dx_lo + (size_t)row * cols + c * V, o);
+                if (dx_hi) store_elems<float, V>(dx_hi + (size_t)row * cols + c * V, o);
             }
         }
     }
@@ -193,23 +197,35 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void colsum_kernel(const T* __restr
     }
 }
 
-// out[i] += sum_p partial[p][i], p ascending.
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int n, float* __restrict__ out) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+// out[i] += sum_p partial[p][i].  A block of 256 threads owns 32 columns: thread
+// (q, c) sums parts q, q+8, q+16, ... of column c with independent loads in
+// flight, then the 8 sub-sums are added in fixed order through LDS.
+// `split` > 0: columns [0, split) go to out, columns [split, n) to out2 (LayerNorm
+// backward keeps dgamma and dbeta partials side by side).
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int n,
+                                                              float* __restrict__ out, float* __restrict__ out2, int split) {
+    __shared__ float red[8][32];
+    const int c = threadIdx.x & 31, q = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + c;
     float s = 0.f;
-    for (int p = 0; p < nparts; ++p) s += partial[(size_t)p * n + i];
-    out[i] += s;
-}
-
-// LayerNorm backward partials hold [block][2][cols]; dgamma and dbeta are separate arrays.
-__global__ void reduce_ln_partials_kernel(const float* __restrict__ partial, int nparts, int cols,
-                                          float* __restrict__ dgamma, float* __restrict__ dbeta) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= 2 * cols) return;
-    float s = 0.f;
-    for (int p = 0; p < nparts; ++p) s += partial[(size_t)p * 2 * cols + i];
-    if (i < cols) dgamma[i] += s; else dbeta[i - cols] += s;
+    if (i < n) {
+        int p = q;
+        for (; p + 24 < nparts; p += 32) {
+            const float a0 = partial[(size_t)p * n + i], a1 = partial[(size_t)(p + 8) * n + i];
+            const float a2 = partial[(size_t)(p + 16) * n + i], a3 = partial[(size_t)(p + 24) * n + i];
+            s += (a0 + a1) + (a2 + a3);
+        }
+        for (; p < nparts; p += 8) s += partial[(size_t)p * n + i];
+    }
+    red[q][c] = s;
+    __syncthreads();
+    if (q == 0 && i < n) {
+        float t = red[0][c];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) t += red[k][c];
+        if (split > 0 && i >= split) out2[i - split] += t;
+        else out[i] += t;
+    }
 }
 
 __global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4, float* __restrict__ tail, int ntail) {
@@ -218,14 +234,14 @@ __global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4, float* __res
     if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0.f;
 }
 
-template <typename T>
+template <typename TX, typename T>
 int ln_fwd_launch(int rows, int cols, const void* x, const void* gamma, const void* beta, void* y, float* mean,
                   float* rstd, hipStream_t s) {
     constexpr int V = Elem<T>::VEC;
     const int per_lane = (cols / V + WAVE - 1) / WAVE;
     const dim3 grid((rows + LN_WAVES - 1) / LN_WAVES), block(LN_WAVES * WAVE);
-#define LN_FWD_CASE(N)                                                                                        \
-    hipLaunchKernelGGL((ln_fwd_kernel<T, N>), grid, block, 0, s, (const T*)x, (const T*)gamma, (const T*)beta, \
+#define LN_FWD_CASE(N)                                                                                             \
+    hipLaunchKernelGGL((ln_fwd_kernel<TX, T, N>), grid, block, 0, s, (const TX*)x, (const T*)gamma, (const T*)beta, \
                        (T*)y, mean, rstd, rows, cols)
     if (per_lane <= 1) LN_FWD_CASE(1);
     else if (per_lane <= 2) LN_FWD_CASE(2);
@@ -237,18 +253,18 @@ int ln_fwd_launch(int rows, int cols, const void* x, const void* gamma, const vo
     return CHIMERA_OK;
 }
 
-template <typename T>
+template <typename TX, typename TR, typename T>
 int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
-                  const void* gamma, const void* res, void* dx, float* dgamma, float* dbeta, float* scratch,
-                  hipStream_t s) {
+                  const void* gamma, const void* res, void* dx_lo, float* dx_hi, float* dgamma, float* dbeta,
+                  float* scratch, hipStream_t s) {
     constexpr int V = Elem<T>::VEC;
     const int per_lane = (cols / V + WAVE - 1) / WAVE;
     const int nblk = (rows + LNB_ROWS - 1) / LNB_ROWS;
     const dim3 grid(nblk), block(LN_WAVES * WAVE);
     const size_t lds = (size_t)2 * cols * sizeof(float);
-#define LN_BWD_CASE(N)                                                                                       \
-    hipLaunchKernelGGL((ln_bwd_kernel<T, N>), grid, block, lds, s, (const T*)dy, (const T*)x, mean, rstd,    \
-                       (const T*)gamma, (const T*)res, (T*)dx, scratch, rows, cols)
+#define LN_BWD_CASE(N)                                                                                              \
+    hipLaunchKernelGGL((ln_bwd_kernel<TX, TR, T, N>), grid, block, lds, s, (const T*)dy, (const TX*)x, mean, rstd,   \
+                       (const T*)gamma, (const TR*)res, (T*)dx_lo, dx_hi, scratch, rows, cols)
     if (per_lane <= 1) LN_BWD_CASE(1);
     else if (per_lane <= 2) LN_BWD_CASE(2);
     else if (per_lane <= 4) LN_BWD_CASE(4);
@@ -256,8 +272,8 @@ int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float
     else return fail(CHIMERA_EINVAL, "LayerNorm width %d too large for the backward (max %d)", cols, 8 * WAVE * V);
 #undef LN_BWD_CASE
     CHIMERA_LAUNCH_CHECK("layernorm backward");
-    hipLaunchKernelGGL(reduce_ln_partials_kernel, dim3((2 * cols + 255) / 256), dim3(256), 0, s, scratch, nblk, cols,
-                       dgamma, dbeta);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * cols + 31) / 32), dim3(256), 0, s, scratch, nblk, 2 * cols,
+                       dgamma, dbeta, cols);
     CHIMERA_LAUNCH_CHECK("layernorm backward reduce");
     return CHIMERA_OK;
 }
@@ -269,7 +285,8 @@ int colsum_launch(int rows, int cols, const void* x, float* out, float* scratch,
     const dim3 grid((cols / V + WAVE - 1) / WAVE, nparts), block(LN_WAVES * WAVE);
     hipLaunchKernelGGL((colsum_kernel<T>), grid, block, 0, s, (const T*)x, scratch, rows, cols);
     CHIMERA_LAUNCH_CHECK("column sum");
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, scratch, nparts, cols, out);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, scratch, nparts, cols, out,
+                       (float*)nullptr, 0);
     CHIMERA_LAUNCH_CHECK("column sum reduce");
     return CHIMERA_OK;
 }
@@ -283,26 +300,30 @@ int check_rowwise(int dtype, int rows, int cols) {
 
 }  // namespace
 
-int layernorm_fwd(int dtype, int rows, int cols, const void* x, const void* gamma, const void* beta, void* y,
+int layernorm_fwd(int dtype, int rows, int cols, const void* x, int x_f32, const void* gamma, const void* beta, void* y,
                   float* mean, float* rstd, void* stream) {
     if (int rc = check_rowwise(dtype, rows, cols)) return rc;
     hipStream_t s = (hipStream_t)stream;
-    return dtype == CHIMERA_F32 ? ln_fwd_launch<float>(rows, cols, x, gamma, beta, y, mean, rstd, s)
-                                : ln_fwd_launch<bf16_t>(rows, cols, x, gamma, beta, y, mean, rstd, s);
+    if (dtype == CHIMERA_F32) return ln_fwd_launch<float, float>(rows, cols, x, gamma, beta, y, mean, rstd, s);
+    return x_f32 ? ln_fwd_launch<float, bf16_t>(rows, cols, x, gamma, beta, y, mean, rstd, s)
+                 : ln_fwd_launch<bf16_t, bf16_t>(rows, cols, x, gamma, beta, y, mean, rstd, s);
 }
 
 size_t layernorm_bwd_scratch_floats(int rows, int cols) {
     return (size_t)((rows + LNB_ROWS - 1) / LNB_ROWS) * 2 * cols;
 }
 
-int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
-                  const void* gamma, const void* res, void* dx, float* dgamma, float* dbeta, float* scratch,
-                  void* stream) {
+int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, int x_f32, const float* mean,
+                  const float* rstd, const void* gamma, const void* res, int res_f32, void* dx_lo, float* dx_hi,
+                  float* dgamma, float* dbeta, float* scratch, void* stream) {
     if (int rc = check_rowwise(dtype, rows, cols)) return rc;
+    if (!dx_lo && !dx_hi) return fail(CHIMERA_EINVAL, "layernorm backward needs an output");
     hipStream_t s = (hipStream_t)stream;
-    return dtype == CHIMERA_F32
-               ? ln_bwd_launch<float>(rows, cols, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, scratch, s)
-               : ln_bwd_launch<bf16_t>(rows, cols, dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta, scratch, s);
+#define LN_BWD_ARGS rows, cols, dy, x, mean, rstd, gamma, res, dx_lo, dx_hi, dgamma, dbeta, scratch, s
+    if (dtype == CHIMERA_F32) return ln_bwd_launch<float, float, float>(LN_BWD_ARGS);
+    if (x_f32) return res_f32 ? ln_bwd_launch<float, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<float, bf16_t, bf16_t>(LN_BWD_ARGS);
+    return res_f32 ? ln_bwd_launch<bf16_t, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<bf16_t, bf16_t, bf16_t>(LN_BWD_ARGS);
+#undef LN_BWD_ARGS
 }
 
 size_t colsum_scratch_floats(int rows, int cols) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * cols; }

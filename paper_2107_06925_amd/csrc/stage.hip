@@ -25,6 +25,46 @@ int fail(int code, const char* fmt, ...) {
 
 static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+// Optional per-kernel-class timing: a HIP event pair around every launch of a
+// class on the stage's stream, summed after the stream has been waited for.
+enum ProfClass { PC_GEMM_FWD, PC_GEMM_DGRAD, PC_GEMM_WGRAD, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD, PC_LN_BWD, PC_COLSUM, PC_COUNT };
+struct ProfRec { hipEvent_t a, b; int cls; double work; };
+struct Profiler {
+    bool on = false;
+    std::vector<ProfRec> recs;
+    double ms[PC_COUNT] = {}, work[PC_COUNT] = {};
+    long long launches[PC_COUNT] = {};
+} g_prof;
+
+struct ProfScope {
+    hipStream_t s; bool live = false; ProfRec r{};
+    ProfScope(int cls, double work, hipStream_t stream) : s(stream) {
+        if (!g_prof.on) return;
+        if (hipEventCreate(&r.a) != hipSuccess) return;
+        if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+        r.cls = cls; r.work = work; live = true;
+        (void)hipEventRecord(r.a, s);
+    }
+    ~ProfScope() {
+        if (!live) return;
+        (void)hipEventRecord(r.b, s);
+        g_prof.recs.push_back(r);
+    }
+};
+
+// Folds finished event pairs into the totals; the stream(s) must be idle.
+static void prof_collect() {
+    for (ProfRec& r : g_prof.recs) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) {
+            g_prof.ms[r.cls] += t; g_prof.work[r.cls] += r.work; ++g_prof.launches[r.cls];
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_prof.recs.clear();
+}
+
 }  // namespace chimera
 
 using namespace chimera;
@@ -45,7 +85,7 @@ struct chimera_stage {
     size_t layer_stash, slot_bytes;
 
     // workspace layout (bytes)
-    size_t w_dy[2], w_du, w_dh, w_dx1, w_dctx, w_dqkv, w_delta, w_scratch, ws_bytes;
+    size_t w_dy[2], w_dyf[2], w_dx1f, w_du, w_dh, w_dx1, w_dctx, w_dqkv, w_delta, w_scratch, ws_bytes;
 
     const char* weights = nullptr;
     float* grads = nullptr;
@@ -85,17 +125,20 @@ void layout(chimera_stage* st) {
     st->s_qkv = takeb(M * 3 * H * e);
     st->s_ctx = takeb(M * H * e);
     st->s_lse = takeb((size_t)st->B * st->heads * st->S * 4);
-    st->s_x1 = takeb(M * H * e);
+    const size_t re = 4;                      // the residual stream between blocks is float in every dtype
+    st->s_x1 = takeb(M * H * re);
     st->s_mean2 = takeb(M * 4); st->s_rstd2 = takeb(M * 4);
     st->s_h2 = takeb(M * H * e);
     st->s_u = takeb(M * 4 * H * e);
     st->s_g = takeb(M * 4 * H * e);
-    st->s_y = takeb(M * H * e);
+    st->s_y = takeb(M * H * re);
     st->layer_stash = b;
     st->slot_bytes = b * st->L;
 
     b = 0;
     st->w_dy[0] = takeb(M * H * e); st->w_dy[1] = takeb(M * H * e);
+    st->w_dyf[0] = takeb(M * H * 4); st->w_dyf[1] = takeb(M * H * 4);
+    st->w_dx1f = takeb(M * H * 4);
     st->w_du = takeb(M * 4 * H * e);
     st->w_dh = takeb(M * H * e);
     st->w_dx1 = takeb(M * H * e);
@@ -107,20 +150,22 @@ void layout(chimera_stage* st) {
     st->ws_bytes = b;
 }
 
-int gemm(chimera_stage* st, const GemmArgs& g) {
+int gemm(chimera_stage* st, const GemmArgs& g, int cls) {
+    ProfScope prof(cls, 2.0 * g.m * g.n * g.k, st->stream);
     if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_supports(g)) return gemm_mfma_bf16(g, st->stream);
     return gemm_reference(st->dtype, g, st->stream);
 }
 
 // C[m,n] = X[m,k] W[k,n] (+ epilogue); W stored [in, out].
 int linear_fwd(chimera_stage* st, int m, int n, int k, const void* x, const void* w, const void* bias, const void* r,
-               void* c, void* c2, int epi) {
+               void* c, void* c2, int epi, int r_f32 = 0, int c_f32 = 0) {
     GemmArgs g{};
     g.m = m; g.n = n; g.k = k;
     g.a = x; g.lda = k; g.a_kc = 1;
     g.b = w; g.ldb = n; g.b_kc = 0;
     g.bias = bias; g.r = r; g.c = c; g.c2 = c2; g.epilogue = epi; g.gelu_erf = st->gelu_erf;
-    return gemm(st, g);
+    g.r_f32 = r_f32; g.c_f32 = c_f32;
+    return gemm(st, g, PC_GEMM_FWD);
 }
 // dX[m,k] = dY[m,n] W^T, W stored [k, n]: contraction over n, contiguous in both.
 int linear_dgrad(chimera_stage* st, int m, int n, int k, const void* dy, const void* w, const void* r, void* dx, int epi) {
@@ -129,7 +174,7 @@ int linear_dgrad(chimera_stage* st, int m, int n, int k, const void* dy, const v
     g.a = dy; g.lda = n; g.a_kc = 1;
     g.b = w; g.ldb = n; g.b_kc = 1;
     g.r = r; g.c = dx; g.epilogue = epi; g.gelu_erf = st->gelu_erf;
-    return gemm(st, g);
+    return gemm(st, g, PC_GEMM_DGRAD);
 }
 // dW[k,n] += X[m,k]^T dY[m,n]: contraction over the tokens.
 int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const void* dy, float* dw) {
@@ -138,7 +183,7 @@ int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const vo
     g.a = x; g.lda = k; g.a_kc = 0;
     g.b = dy; g.ldb = n; g.b_kc = 0;
     g.c = dw; g.epilogue = EPI_ACCUM_F32;
-    return gemm(st, g);
+    return gemm(st, g, PC_GEMM_WGRAD);
 }
 
 int attn_args(chimera_stage* st, AttnArgs& a) {
@@ -148,12 +193,50 @@ int attn_args(chimera_stage* st, AttnArgs& a) {
 
 #define TRY(expr) do { int rc__ = (expr); if (rc__) return rc__; } while (0)
 
+// useful attention flop: 4 S^2 d per (sequence, head) forward (x 1/2 causal, exactly (S+1)/(2S)), 2x that backward
+double attn_flop(const chimera_stage* st) {
+    const double c = st->causal ? (st->S + 1.0) / (2.0 * st->S) : 1.0;
+    return 4.0 * st->M * (double)st->S * st->H * c;
+}
+int st_attn_fwd(chimera_stage* st, const AttnArgs& a) {
+    ProfScope prof(PC_ATTN_FWD, attn_flop(st), st->stream);
+    if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && attention_mfma_supports(a)) return attention_fwd_mfma(a, st->stream);
+    return attention_fwd_reference(st->dtype, a, st->stream);
+}
+int st_attn_bwd(chimera_stage* st, const AttnArgs& a) {
+    ProfScope prof(PC_ATTN_BWD, 2.0 * attn_flop(st), st->stream);
+    if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && attention_mfma_supports(a)) return attention_bwd_mfma(a, st->stream);
+    return attention_bwd_reference(st->dtype, a, st->stream);
+}
+// algorithmic bytes of the row-wise kernels: every operand once, at the width it is stored in
+int st_ln_fwd(chimera_stage* st, const void* x, int x_f32, const void* g, const void* b, void* y, float* mean, float* rstd) {
+    ProfScope prof(PC_LN_FWD, (double)st->M * st->H * ((x_f32 ? 4 : st->esz) + st->esz), st->stream);
+    return layernorm_fwd(st->dtype, st->M, st->H, x, x_f32, g, b, y, mean, rstd, st->stream);
+}
+int st_ln_bwd(chimera_stage* st, const void* dy, const void* x, int x_f32, const float* mean, const float* rstd,
+              const void* g, const void* res, int res_f32, void* dx_lo, float* dx_hi, float* dg, float* db, float* scratch) {
+    const double bytes = st->esz + (x_f32 ? 4 : st->esz) + (res_f32 ? 4 : st->esz) + (dx_lo ? st->esz : 0) + (dx_hi ? 4 : 0);
+    ProfScope prof(PC_LN_BWD, (double)st->M * st->H * bytes, st->stream);
+    return layernorm_bwd(st->dtype, st->M, st->H, dy, x, x_f32, mean, rstd, g, res, res_f32, dx_lo, dx_hi, dg, db, scratch,
+                         st->stream);
+}
+int st_colsum(chimera_stage* st, int cols, const void* x, float* out, float* scratch) {
+    ProfScope prof(PC_COLSUM, (double)st->M * cols * st->esz, st->stream);
+    return colsum(st->dtype, st->M, cols, x, out, scratch, st->stream);
+}
+
+// Inside a bf16 stage the residual stream (x -> x1 -> y of every block) stays in
+// float: a bf16 stream would be re-rounded at each of the 2L residual additions and
+// that random walk, not the matrix products, would dominate the stage's error.
+// Only the stage's own input and output are in the stage dtype.
 int stage_forward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
     const int M = st->M, H = st->H, L = st->L;
-    void* s = st->stream;
+    const int wide = st->dtype == CHIMERA_BF16;       // float stream differs from the stage dtype
     for (int l = 0; l < L; ++l) {
         const void* x = l == 0 ? io.x : st->ST(slot, l - 1, st->s_y);
+        const int x_f32 = wide && l > 0;
         void* y = l == L - 1 ? io.y : st->ST(slot, l, st->s_y);
+        const int y_f32 = wide && l < L - 1;
         void* h1 = st->ST(slot, l, st->s_h1);
         void* qkv = st->ST(slot, l, st->s_qkv);
         void* ctx = st->ST(slot, l, st->s_ctx);
@@ -161,36 +244,43 @@ int stage_forward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         void* h2 = st->ST(slot, l, st->s_h2);
         void* u = st->ST(slot, l, st->s_u);
         void* g = st->ST(slot, l, st->s_g);
-        TRY(layernorm_fwd(st->dtype, M, H, x, st->W(l, st->o_ln1_g), st->W(l, st->o_ln1_b), h1,
-                          (float*)st->ST(slot, l, st->s_mean1), (float*)st->ST(slot, l, st->s_rstd1), s));
+        TRY(st_ln_fwd(st, x, x_f32, st->W(l, st->o_ln1_g), st->W(l, st->o_ln1_b), h1, (float*)st->ST(slot, l, st->s_mean1),
+                      (float*)st->ST(slot, l, st->s_rstd1)));
         TRY(linear_fwd(st, M, 3 * H, H, h1, st->W(l, st->o_w_qkv), st->W(l, st->o_b_qkv), nullptr, qkv, nullptr, EPI_BIAS));
         AttnArgs a{};
         attn_args(st, a);
         a.qkv = qkv; a.ctx = ctx; a.lse = (float*)st->ST(slot, l, st->s_lse);
-        if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && attention_mfma_supports(a)) TRY(attention_fwd_mfma(a, s));
-        else TRY(attention_fwd_reference(st->dtype, a, s));
-        TRY(linear_fwd(st, M, H, H, ctx, st->W(l, st->o_w_o), st->W(l, st->o_b_o), x, x1, nullptr, EPI_BIAS_RESIDUAL));
-        TRY(layernorm_fwd(st->dtype, M, H, x1, st->W(l, st->o_ln2_g), st->W(l, st->o_ln2_b), h2,
-                          (float*)st->ST(slot, l, st->s_mean2), (float*)st->ST(slot, l, st->s_rstd2), s));
+        TRY(st_attn_fwd(st, a));
+        TRY(linear_fwd(st, M, H, H, ctx, st->W(l, st->o_w_o), st->W(l, st->o_b_o), x, x1, nullptr, EPI_BIAS_RESIDUAL, x_f32, wide));
+        TRY(st_ln_fwd(st, x1, wide, st->W(l, st->o_ln2_g), st->W(l, st->o_ln2_b), h2, (float*)st->ST(slot, l, st->s_mean2),
+                      (float*)st->ST(slot, l, st->s_rstd2)));
         TRY(linear_fwd(st, M, 4 * H, H, h2, st->W(l, st->o_w_fc1), st->W(l, st->o_b_fc1), nullptr, u, g, EPI_BIAS_GELU));
-        TRY(linear_fwd(st, M, H, 4 * H, g, st->W(l, st->o_w_fc2), st->W(l, st->o_b_fc2), x1, y, nullptr, EPI_BIAS_RESIDUAL));
+        TRY(linear_fwd(st, M, H, 4 * H, g, st->W(l, st->o_w_fc2), st->W(l, st->o_b_fc2), x1, y, nullptr, EPI_BIAS_RESIDUAL, wide, y_f32));
     }
     return CHIMERA_OK;
 }
 
+// The gradient of the residual stream is float as well (dy -> dx1 -> dx); each
+// LayerNorm backward also writes a copy in the stage dtype, which is what the
+// matrix-core products and the bias sums read.
 int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
     const int M = st->M, H = st->H, L = st->L;
-    void* s = st->stream;
+    const int wide = st->dtype == CHIMERA_BF16;
     float* scratch = (float*)(st->ws + st->w_scratch);
     void* du = st->ws + st->w_du;
     void* dh = st->ws + st->w_dh;
     void* dx1 = st->ws + st->w_dx1;
+    float* dx1f = wide ? (float*)(st->ws + st->w_dx1f) : nullptr;
     void* dctx = st->ws + st->w_dctx;
     void* dqkv = st->ws + st->w_dqkv;
-    const void* dy = io.dy;
+    const void* dy = io.dy;           // stage dtype: operand of the products
+    const void* dyr = io.dy;          // what the residual path adds (float inside a bf16 stage)
+    int dyr_f32 = 0;
     for (int l = L - 1; l >= 0; --l) {
         const void* x = l == 0 ? io.x : st->ST(slot, l - 1, st->s_y);
+        const int x_f32 = wide && l > 0;
         void* dx = l == 0 ? io.dx : (void*)(st->ws + st->w_dy[l & 1]);
+        float* dxf = (wide && l > 0) ? (float*)(st->ws + st->w_dyf[l & 1]) : nullptr;
         const void* h1 = st->ST(slot, l, st->s_h1);
         const void* qkv = st->ST(slot, l, st->s_qkv);
         const void* ctx = st->ST(slot, l, st->s_ctx);
@@ -199,34 +289,34 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         const void* u = st->ST(slot, l, st->s_u);
         const void* g = st->ST(slot, l, st->s_g);
         // y = x1 + g W2 + b2
-        TRY(colsum(st->dtype, M, H, dy, st->G(l, st->o_b_fc2), scratch, s));
+        TRY(st_colsum(st, H, dy, st->G(l, st->o_b_fc2), scratch));
         TRY(linear_wgrad(st, M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2)));
         TRY(linear_dgrad(st, M, H, 4 * H, dy, st->W(l, st->o_w_fc2), u, du, EPI_DGELU));       // du = dg * GeLU'(u)
         // u = h2 W1 + b1
-        TRY(colsum(st->dtype, M, 4 * H, du, st->G(l, st->o_b_fc1), scratch, s));
+        TRY(st_colsum(st, 4 * H, du, st->G(l, st->o_b_fc1), scratch));
         TRY(linear_wgrad(st, M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1)));
         TRY(linear_dgrad(st, M, 4 * H, H, du, st->W(l, st->o_w_fc1), nullptr, dh, EPI_NONE));
-        TRY(layernorm_bwd(st->dtype, M, H, dh, x1, (const float*)st->ST(slot, l, st->s_mean2),
-                          (const float*)st->ST(slot, l, st->s_rstd2), st->W(l, st->o_ln2_g), dy, dx1,
-                          st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch, s));
+        TRY(st_ln_bwd(st, dh, x1, wide, (const float*)st->ST(slot, l, st->s_mean2), (const float*)st->ST(slot, l, st->s_rstd2),
+                      st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch));
         // x1 = x + ctx Wo + bo
-        TRY(colsum(st->dtype, M, H, dx1, st->G(l, st->o_b_o), scratch, s));
+        TRY(st_colsum(st, H, dx1, st->G(l, st->o_b_o), scratch));
         TRY(linear_wgrad(st, M, H, H, ctx, dx1, st->G(l, st->o_w_o)));
         TRY(linear_dgrad(st, M, H, H, dx1, st->W(l, st->o_w_o), nullptr, dctx, EPI_NONE));
         AttnArgs a{};
         attn_args(st, a);
         a.qkv = qkv; a.ctx = (void*)ctx; a.lse = (float*)st->ST(slot, l, st->s_lse);
         a.dctx = dctx; a.dqkv = dqkv; a.delta = (float*)(st->ws + st->w_delta);
-        if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && attention_mfma_supports(a)) TRY(attention_bwd_mfma(a, s));
-        else TRY(attention_bwd_reference(st->dtype, a, s));
+        TRY(st_attn_bwd(st, a));
         // qkv = h1 Wqkv + bqkv
-        TRY(colsum(st->dtype, M, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch, s));
+        TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch));
         TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv)));
         TRY(linear_dgrad(st, M, 3 * H, H, dqkv, st->W(l, st->o_w_qkv), nullptr, dh, EPI_NONE));
-        TRY(layernorm_bwd(st->dtype, M, H, dh, x, (const float*)st->ST(slot, l, st->s_mean1),
-                          (const float*)st->ST(slot, l, st->s_rstd1), st->W(l, st->o_ln1_g), dx1, dx,
-                          st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch, s));
+        TRY(st_ln_bwd(st, dh, x, x_f32, (const float*)st->ST(slot, l, st->s_mean1), (const float*)st->ST(slot, l, st->s_rstd1),
+                      st->W(l, st->o_ln1_g), wide ? (const void*)dx1f : (const void*)dx1, wide, dx, dxf,
+                      st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch));
         dy = dx;
+        dyr = dxf ? (const void*)dxf : (const void*)dx;
+        dyr_f32 = dxf != nullptr;
     }
     return CHIMERA_OK;
 }
@@ -441,6 +531,27 @@ int chimera_worker_last_timing(double* h_fwd_ms, double* h_bwd_ms, int* h_nf, in
     return CHIMERA_OK;
 }
 
+int chimera_profile_enable(int on) {
+    if (!g_prof.recs.empty()) prof_collect();
+    g_prof.on = on != 0;
+    return CHIMERA_OK;
+}
+
+int chimera_profile_reset(void) {
+    prof_collect();
+    for (int c = 0; c < PC_COUNT; ++c) { g_prof.ms[c] = 0; g_prof.work[c] = 0; g_prof.launches[c] = 0; }
+    return CHIMERA_OK;
+}
+
+int chimera_profile_read(int cls, double* h_ms, long long* h_launches, double* h_work) {
+    if (cls < 0 || cls >= PC_COUNT) return fail(CHIMERA_EINVAL, "profile class %d outside [0,%d)", cls, (int)PC_COUNT);
+    prof_collect();
+    if (h_ms) *h_ms = g_prof.ms[cls];
+    if (h_launches) *h_launches = g_prof.launches[cls];
+    if (h_work) *h_work = g_prof.work[cls];
+    return CHIMERA_OK;
+}
+
 // ------------------------------------------------------------ single operators
 int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int n, int k, const void* d_a, int lda,
                     int a_kc, const void* d_b, int ldb, int b_kc, const void* d_bias, const void* d_r, void* d_c,
@@ -465,7 +576,7 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x, const void* d_gamma, const void* d_beta,
                              void* d_y, float* d_mean, float* d_rstd, void* hip_stream) {
     if (!d_x || !d_gamma || !d_beta || !d_y || !d_mean || !d_rstd) return fail(CHIMERA_EINVAL, "NULL operand");
-    return layernorm_fwd(dtype, rows, cols, d_x, d_gamma, d_beta, d_y, d_mean, d_rstd, hip_stream);
+    return layernorm_fwd(dtype, rows, cols, d_x, 0, d_gamma, d_beta, d_y, d_mean, d_rstd, hip_stream);
 }
 
 size_t chimera_op_layernorm_bwd_scratch_floats(int rows, int cols) { return layernorm_bwd_scratch_floats(rows, cols); }
@@ -475,7 +586,8 @@ int chimera_op_layernorm_bwd(int dtype, int rows, int cols, const void* d_dy, co
                              float* d_dbeta, float* d_scratch, void* hip_stream) {
     if (!d_dy || !d_x || !d_mean || !d_rstd || !d_gamma || !d_res || !d_dx || !d_dgamma || !d_dbeta || !d_scratch)
         return fail(CHIMERA_EINVAL, "NULL operand");
-    return layernorm_bwd(dtype, rows, cols, d_dy, d_x, d_mean, d_rstd, d_gamma, d_res, d_dx, d_dgamma, d_dbeta, d_scratch, hip_stream);
+    return layernorm_bwd(dtype, rows, cols, d_dy, d_x, 0, d_mean, d_rstd, d_gamma, d_res, 0, d_dx, nullptr, d_dgamma, d_dbeta, d_scratch,
+                         hip_stream);
 }
 
 size_t chimera_op_colsum_scratch_floats(int rows, int cols) { return colsum_scratch_floats(rows, cols); }

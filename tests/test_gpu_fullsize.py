@@ -1,0 +1,79 @@
+"""Parity at the workloads' full sizes, in the launch configuration bench.py times.
+
+The oracle needs about 20 s per micro-batch and stage at these sizes, so the
+whole-worker check uses a property that holds at any size: parameter gradients
+are linear in the upstream gradients, so with dY = 0 for every micro-batch but
+one per stage the accumulated gradients must equal the oracle's for that one
+micro-batch, while Y of those micro-batches is unaffected by what the others do.
+"""
+import numpy as np
+import pytest
+
+from oracle import block_oracle as bo
+from paper_2107_06925_amd import binding as b
+from paper_2107_06925_amd import synth
+from gpu_util import assert_close, compare_grads, make_stage, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def test_bert48_worker_full_size():
+    """BERT-48-like worker exactly as benchmarked: D=4, N=4, rank 0, 12 blocks per stage,
+    hidden 1024, 16 heads, seq 512, micro-batch 8, bidirectional, bf16."""
+    import torch
+    cfg = synth.CONFIGS["bert48-bf16"]
+    rank, D, N = 0, cfg.D, cfg.N
+    need = b.stash_slots_needed(b.DIRECT, D, N, rank)
+    assert need == (2, 1)
+    gain = 1.0                        # the workload's own recipe, as benchmarked
+    stages, params = [], []
+    for pipe, sid in ((0, rank), (1, D - 1 - rank)):
+        st, p = make_stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, b.BF16, sid, causal=cfg.causal,
+                           stash_slots=need[pipe], qk_gain=gain)
+        stages.append(st), params.append(p)
+    sampled = {0: 0, 1: 3}            # pipe -> micro-batch whose dY is kept
+    xs, dys, outs = {}, {}, {}
+    for g in range(N):
+        x, dy = synth.make_microbatch(cfg.tokens, cfg.hidden, g, 0, "bf16")
+        pipe = 0 if (g % D) < D // 2 else 1
+        if sampled[pipe] != g:
+            dy = np.zeros_like(dy)
+        xs[g], dys[g] = x, dy
+        outs[g] = stages[pipe].set_io(g, to_dev(x, b.BF16), to_dev(dy, b.BF16))
+    b.chimera_worker_bind(stages[0], stages[1])
+    for st in stages:
+        st.zero_grads()
+    b.chimera_run_worker(rank, D, N)
+    torch.cuda.synchronize()
+    for pipe, g in sampled.items():
+        print("oracle: stage pass of micro-batch", g, flush=True)
+        y, dx, gr = bo.stage_pass(xs[g], dys[g], params[pipe], cfg.microbatch, cfg.seq, cfg.heads, cfg.causal)
+        ey = assert_close(to_np(outs[g][0]), y, b.BF16, "y of micro-batch %d" % g)
+        ex = assert_close(to_np(outs[g][1]), dx, b.BF16, "dx of micro-batch %d" % g)
+        print("micro-batch %d: y rel err %.3e, dx rel err %.3e" % (g, ey, ex), flush=True)
+        eg = compare_grads(stages[pipe].read_grads(), gr, cfg.layers, cfg.hidden, b.BF16, "stage of pipe %d" % pipe)
+        print("pipe %d: worst parameter-gradient rel err %.3e" % (pipe, eg), flush=True)
+    # micro-batches with dY = 0 give dX = 0 exactly
+    assert float(outs[1][1].float().abs().max()) == 0.0
+    for st in stages:
+        st.close()
+
+
+@pytest.mark.parametrize("name", ["gpt2-1p3b-bf16", "gpt2-1p3b-n32-bf16", "gpt2-deep-bf16"])
+def test_gpt2_shapes_one_block(name):
+    """One block at the full token count and width of the GPT-2-like workloads
+    (hidden 1600 / 25 heads, and hidden 2048 / head_dim 128 / seq 2048), causal."""
+    import torch
+    cfg = synth.CONFIGS[name]
+    st, params = make_stage(1, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, b.BF16, 0, causal=True,
+                            qk_gain=synth.qk_gain_for(cfg.hidden))
+    x, dy = synth.make_microbatch(cfg.tokens, cfg.hidden, 0, 0, "bf16")
+    y, dx = st.set_io(0, to_dev(x, b.BF16), to_dev(dy, b.BF16))
+    st.fwd(0)
+    st.bwd(0)
+    torch.cuda.synchronize()
+    y64, dx64, gr = bo.stage_pass(x, dy, params, cfg.microbatch, cfg.seq, cfg.heads, True)
+    assert_close(to_np(y), y64, b.BF16, "y")
+    assert_close(to_np(dx), dx64, b.BF16, "dx")
+    compare_grads(st.read_grads(), gr, 1, cfg.hidden, b.BF16)
+    st.close()
