@@ -68,8 +68,11 @@ enum { CHIMERA_DIRECT = 0, CHIMERA_GPIPE = 1, CHIMERA_1F1B = 2 };
 enum {
     CHIMERA_OPT_CAUSAL = 0,  /* 1 (default) = causal mask, 0 = bidirectional        */
     CHIMERA_OPT_GELU = 1,    /* 0 (default) = tanh form, 1 = exact erf form         */
-    CHIMERA_OPT_KERNELS = 2  /* 0 (default) = matrix-core kernels where the shape   */
+    CHIMERA_OPT_KERNELS = 2, /* 0 (default) = matrix-core kernels where the shape   */
                              /* allows, 1 = plain reference kernels everywhere      */
+    CHIMERA_OPT_OVERLAP = 3  /* 1 (default) = weight and bias gradients of a        */
+                             /* backward run on a second stream of the stage's own, */
+                             /* beside the input-gradient chain; 0 = one stream     */
 };
 
 typedef struct chimera_stage chimera_stage;
@@ -203,13 +206,21 @@ int chimera_profile_read(int cls, double* h_ms, long long* h_launches, double* h
  * epilogue: 0 C = acc (dtype); 1 C = acc + bias[n]; 2 C = acc + bias[n] and
  * C2 = GeLU(C); 3 C = acc + bias[n] + R[m,n]; 4 C = acc * GeLU'(R[m,n]);
  * 5 C (float, always) += acc.  C, C2, R have leading dimension n.
- * EINVAL if k, n or a leading dimension is not a multiple of 8. */
+ * EINVAL if k, n or a leading dimension is not a multiple of 8.
+ * d_workspace (may be NULL): chimera_op_gemm_workspace_bytes(m, n, k) bytes, 256-byte
+ * aligned, whose first 4096 bytes are zero before the first call; with it, and with the
+ * environment variable CHIMERA_GEMM_TILE=256x256x<splits> (a tuning aid), the bf16
+ * kernel splits the k range over several workgroups per tile (partial sums are added in
+ * a fixed order, so results stay reproducible).  Concurrent calls need separate
+ * workspaces.  Without it every product runs unsplit. */
+size_t chimera_op_gemm_workspace_bytes(int m, int n, int k);
 int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind,
                     int m, int n, int k,
                     const void* d_a, int lda, int a_kc,
                     const void* d_b, int ldb, int b_kc,
                     const void* d_bias, const void* d_r,
-                    void* d_c, void* d_c2, void* hip_stream);
+                    void* d_c, void* d_c2, void* d_workspace, size_t workspace_bytes,
+                    void* hip_stream);
 /* y = LN(x) gamma + beta; mean, rstd [rows] float are written for the backward. */
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x,
                              const void* d_gamma, const void* d_beta, void* d_y,

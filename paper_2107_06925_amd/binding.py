@@ -10,7 +10,7 @@ LIB_PATH = os.path.join(HERE, "libchimera.so")
 OK, EINVAL, ENOMEM, ESTATE, EDEVICE = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
 DIRECT, GPIPE, ONE_F_ONE_B = 0, 1, 2
-OPT_CAUSAL, OPT_GELU, OPT_KERNELS = 0, 1, 2
+OPT_CAUSAL, OPT_GELU, OPT_KERNELS, OPT_OVERLAP = 0, 1, 2, 3
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL, EPI_DGELU, EPI_ACCUM_F32 = range(6)
 
 
@@ -57,7 +57,8 @@ _SIGNATURES = {
     "chimera_profile_enable": (_i, [_i]),
     "chimera_profile_reset": (_i, []),
     "chimera_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
-    "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p]),
+    "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
+    "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_bwd_scratch_floats": (_sz, [_i, _i]),
     "chimera_op_layernorm_bwd": (_i, [_i, _i, _i] + [_p] * 11),
@@ -122,7 +123,7 @@ class Stage:
     """Owns the device buffers (torch tensors) a chimera_stage borrows."""
 
     def __init__(self, layers, hidden, heads, seq, microbatch, dtype, causal=True, gelu_erf=False,
-                 reference_kernels=False, stash_slots=1, stream=None, device="cuda:0"):
+                 reference_kernels=False, stash_slots=1, stream=None, device="cuda:0", overlap=True):
         import torch
         self.torch = torch
         self.handle = lib().chimera_stage_create(layers, hidden, heads, seq, microbatch, dtype)
@@ -132,6 +133,7 @@ class Stage:
         check(lib().chimera_stage_set_option(self.handle, OPT_CAUSAL, int(bool(causal))))
         check(lib().chimera_stage_set_option(self.handle, OPT_GELU, int(bool(gelu_erf))))
         check(lib().chimera_stage_set_option(self.handle, OPT_KERNELS, int(bool(reference_kernels))))
+        check(lib().chimera_stage_set_option(self.handle, OPT_OVERLAP, int(bool(overlap))))
         self.tdtype = torch.float32 if dtype == F32 else torch.bfloat16
         esz = 4 if dtype == F32 else 2
         L = lib()
@@ -251,12 +253,28 @@ def _dt(t):
     return F32 if t.dtype == torch.float32 else BF16
 
 
+_gemm_ws = {}
+
+
+def gemm_workspace(m, n, k, device):
+    """A zero-initialised split-K workspace for this shape (cached per size), or None."""
+    import torch
+    need = lib().chimera_op_gemm_workspace_bytes(m, n, k)
+    if not need:
+        return None
+    if need not in _gemm_ws:
+        _gemm_ws[need] = torch.zeros(need, dtype=torch.uint8, device=device)
+    return _gemm_ws[need]
+
+
 def chimera_op_gemm(a, b, c, m, n, k, a_kc, b_kc, epilogue=EPI_NONE, bias=None, r=None, c2=None, impl=0,
-                    gelu_erf=False, lda=None, ldb=None):
+                    gelu_erf=False, lda=None, ldb=None, workspace="auto"):
     lda = lda if lda is not None else (k if a_kc else m)
     ldb = ldb if ldb is not None else (k if b_kc else n)
+    ws = gemm_workspace(m, n, k, a.device) if isinstance(workspace, str) else workspace
     check(lib().chimera_op_gemm(_dt(a), impl, epilogue, int(gelu_erf), m, n, k, _ptr(a), lda, int(a_kc), _ptr(b), ldb,
-                                int(b_kc), _ptr(bias), _ptr(r), _ptr(c), _ptr(c2), _stream(a)))
+                                int(b_kc), _ptr(bias), _ptr(r), _ptr(c), _ptr(c2), _ptr(ws),
+                                ws.numel() if ws is not None else 0, _stream(a)))
 
 
 def chimera_op_layernorm_fwd(x, gamma, beta, y, mean, rstd):

@@ -42,6 +42,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;
 constexpr int GROUP_M = 8;       // tile rows per raster group
+constexpr size_t SPLITK_COUNTER_BYTES = 4096;
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
 
@@ -53,28 +54,34 @@ __device__ __forceinline__ unsigned half_of(const uint4& q, int t) {
 // k rows per transposing unit: 8 when every thread then still has a unit, else 4
 template <int ROWS, int NT> struct McShape {
     static constexpr int KB = (ROWS * BK / 64 >= NT) ? 8 : 4;
-    static constexpr int UPT = ROWS * BK / (8 * KB * NT);   // units per thread
-    static_assert(UPT >= 1, "tile too small for the workgroup");
+    static constexpr int UNITS = ROWS * BK / (8 * KB);      // 8 x KB element blocks in the tile
+    static constexpr int UPT = (UNITS + NT - 1) / NT;       // units per thread (threads beyond UNITS idle)
 };
 template <int ROWS, int NT, bool KC> struct Staged {
     static constexpr int N = KC ? ROWS * (BK / 8) / NT : McShape<ROWS, NT>::UPT * McShape<ROWS, NT>::KB;
     uint4 v[N];
+    unsigned ok;     // bit i: v[i] lies inside the matrix (others are zeroed when written to LDS)
 };
 
 // global -> registers for one operand tile of ROWS rows x BK k values.
 // KC: element (row, k) at base[row * ld + k].  !KC: at base[k * ld + row].
+// Loads are unconditional (an out-of-range piece reads element 0 instead and is
+// zeroed later), so no branch separates the loads of different k steps and they
+// can stay in flight across steps.
 template <int ROWS, int NT, bool KC>
 __device__ __forceinline__ void load_tile(Staged<ROWS, NT, KC>& st, const bf16_t* __restrict__ base, int ld, int row0,
                                           int nrows, int k0, int K, int tid) {
+    unsigned okm = 0;
     if constexpr (KC) {
         constexpr int CPT = ROWS * (BK / 8) / NT;
 #pragma unroll
         for (int it = 0; it < CPT; ++it) {
             const int c = tid + it * NT;
             const int gr = row0 + (c >> 3), gk = k0 + (c & 7) * 8;
-            uint4 q = make_uint4(0u, 0u, 0u, 0u);
-            if (gr < nrows && gk < K) q = *reinterpret_cast<const uint4*>(base + (size_t)gr * ld + gk);
-            st.v[it] = q;
+            const bool ok = gr < nrows && gk < K;
+            const unsigned off = ok ? (unsigned)gr * (unsigned)ld + (unsigned)gk : 0u;
+            st.v[it] = *reinterpret_cast<const uint4*>(base + off);
+            okm |= (ok ? 1u : 0u) << it;
         }
     } else {
         constexpr int KB = McShape<ROWS, NT>::KB, UPT = McShape<ROWS, NT>::UPT, IG = ROWS / 8;
@@ -82,14 +89,22 @@ __device__ __forceinline__ void load_tile(Staged<ROWS, NT, KC>& st, const bf16_t
         for (int it = 0; it < UPT; ++it) {
             const int u = tid + it * NT;
             const int gi = row0 + (u % IG) * 8, kb = k0 + (u / IG) * KB;
+            const bool mine = (McShape<ROWS, NT>::UNITS % NT == 0 || u < McShape<ROWS, NT>::UNITS) && gi < nrows;
 #pragma unroll
             for (int r = 0; r < KB; ++r) {
-                uint4 q = make_uint4(0u, 0u, 0u, 0u);
-                if (gi < nrows && kb + r < K) q = *reinterpret_cast<const uint4*>(base + (size_t)(kb + r) * ld + gi);
-                st.v[it * KB + r] = q;
+                const bool ok = mine && kb + r < K;
+                const unsigned off = ok ? (unsigned)(kb + r) * (unsigned)ld + (unsigned)gi : 0u;
+                st.v[it * KB + r] = *reinterpret_cast<const uint4*>(base + off);
+                okm |= (ok ? 1u : 0u) << (it * KB + r);
             }
         }
     }
+    st.ok = okm;
+}
+
+__device__ __forceinline__ uint4 keep_if(const uint4& q, unsigned mask, int bit) {
+    const bool ok = (mask >> bit) & 1u;
+    return make_uint4(ok ? q.x : 0u, ok ? q.y : 0u, ok ? q.z : 0u, ok ? q.w : 0u);
 }
 
 // registers -> LDS tile [ROWS][BK], swizzled.
@@ -101,23 +116,26 @@ __device__ __forceinline__ void store_tile(const Staged<ROWS, NT, KC>& st, bf16_
         for (int it = 0; it < CPT; ++it) {
             const int c = tid + it * NT;
             const int row = c >> 3, kc = c & 7;
-            *reinterpret_cast<uint4*>(lds + row * BK + swz(row, kc) * 8) = st.v[it];
+            *reinterpret_cast<uint4*>(lds + row * BK + swz(row, kc) * 8) = keep_if(st.v[it], st.ok, it);
         }
     } else {
         constexpr int KB = McShape<ROWS, NT>::KB, UPT = McShape<ROWS, NT>::UPT, IG = ROWS / 8;
 #pragma unroll
         for (int it = 0; it < UPT; ++it) {
             const int u = tid + it * NT;
+            if (McShape<ROWS, NT>::UNITS % NT != 0 && u >= McShape<ROWS, NT>::UNITS) continue;
             const int ig = u % IG, kg = u / IG;
             const int chunk = (kg * KB) >> 3, within = (kg * KB) & 7;
+            uint4 q[KB];
+#pragma unroll
+            for (int r = 0; r < KB; ++r) q[r] = keep_if(st.v[it * KB + r], st.ok, it * KB + r);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const int row = ig * 8 + t;
                 bf16_t* dst = lds + row * BK + swz(row, chunk) * 8 + within;
                 unsigned w[KB / 2];
 #pragma unroll
-                for (int p = 0; p < KB / 2; ++p)
-                    w[p] = half_of(st.v[it * KB + 2 * p], t) | (half_of(st.v[it * KB + 2 * p + 1], t) << 16);
+                for (int p = 0; p < KB / 2; ++p) w[p] = half_of(q[2 * p], t) | (half_of(q[2 * p + 1], t) << 16);
                 if constexpr (KB == 8) *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
                 else *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
             }
@@ -167,18 +185,21 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], int row_ba
 }
 
 template <int BM, int BN, int WGM, int WGN, int PF, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(BM * BN <= 128 * 128 ? 2 : 1, 2))) void gemm_bf16_kernel(
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n) {
+    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n, int splits, float* __restrict__ slabs,
+    unsigned* __restrict__ arrivals) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;    // wavefront tile
     constexpr int TM = WM / 32, TN = WN / 32;      // MFMA tiles per wavefront
     __shared__ __attribute__((aligned(16))) bf16_t lds[2][(BM + BN) * BK];
 
     // workgroup id -> tile, XCD-contiguous then grouped raster
+    // With split-K the grid holds `splits` workgroups per tile: split = blockIdx / tiles.
     const int nblk = tiles_m * tiles_n;
-    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int split = blockIdx.x / nblk, bid = blockIdx.x % nblk;
+    const int xcd = bid & 7, local = bid >> 3;
     const int pid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
     const int width = GROUP_M * tiles_n;
     const int first_m = (pid / width) * GROUP_M;
@@ -232,40 +253,74 @@ __global__ __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(B
         store_tile<BN, NT, B_KC>(rb, lds[buf] + BM * BK, tid);
     };
 
-    const int KT = (k + BK - 1) / BK;
-    if constexpr (PF == 1) {
-        // global loads run one k step ahead of the matrix cores
-        Staged<BM, NT, A_KC> ra;
-        Staged<BN, NT, B_KC> rb;
-        fetch(ra, rb, 0);
-        stash(ra, rb, 0);
-        __syncthreads();
-        for (int kt = 0; kt < KT; ++kt) {
-            const int buf = kt & 1;
-            if (kt + 1 < KT) fetch(ra, rb, kt + 1);
-            compute(buf);
-            if (kt + 1 < KT) stash(ra, rb, buf ^ 1);
+    // Software pipeline: global loads run PF k steps ahead of the matrix cores in PF
+    // register sets (a ring walked by an unrolled loop, so every index is static),
+    // LDS runs one step ahead in two buffers, one barrier per step.
+    // This workgroup's share of the k steps: [K0, K1).
+    const int KT_all = (k + BK - 1) / BK;
+    const int K0 = (int)((long)KT_all * split / splits), K1 = (int)((long)KT_all * (split + 1) / splits);
+    const int KT = K1 - K0;
+    Staged<BM, NT, A_KC> ra[PF];
+    Staged<BN, NT, B_KC> rb[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u < KT) fetch(ra[u], rb[u], K0 + u);
+    stash(ra[0], rb[0], 0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int step = kt + u;
+            if (step >= KT) break;
+            if (step + PF < KT) fetch(ra[u], rb[u], K0 + step + PF);      // set u was stashed one step ago
+            compute(step & 1);
+            if (step + 1 < KT) stash(ra[(u + 1) % PF], rb[(u + 1) % PF], (step + 1) & 1);
             __syncthreads();
         }
-    } else {
-        // global loads run two k steps ahead (two register sets), LDS one step ahead
-        Staged<BM, NT, A_KC> ra0, ra1;
-        Staged<BN, NT, B_KC> rb0, rb1;
-        fetch(ra0, rb0, 0);
-        if (KT > 1) fetch(ra1, rb1, 1);
-        stash(ra0, rb0, 0);
+    }
+
+    // Split-K: every workgroup of a tile writes its partial accumulators to its own slab
+    // (thread-private order, 16-byte stores), then counts itself in.  Whoever arrives last
+    // adds the slabs in split order - so the sum does not depend on who that is - and runs
+    // the epilogue.  Nobody waits for anybody.
+    if (splits > 1) {
+        __shared__ int is_last;
+        const size_t tile_elems = (size_t)BM * BN;
+        float4* mine = reinterpret_cast<float4*>(slabs + ((size_t)split * nblk + pid) * tile_elems);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    mine[((a * TN + b) * 4 + q) * NT + tid] =
+                        make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+        __threadfence();                       // slab visible device-wide before the arrival count
         __syncthreads();
-        for (int kt = 0; kt < KT; kt += 2) {
-            if (kt + 2 < KT) fetch(ra0, rb0, kt + 2);
-            compute(0);
-            if (kt + 1 < KT) stash(ra1, rb1, 1);
-            __syncthreads();
-            if (kt + 1 >= KT) break;
-            if (kt + 3 < KT) fetch(ra1, rb1, kt + 3);
-            compute(1);
-            if (kt + 2 < KT) stash(ra0, rb0, 0);
-            __syncthreads();
+        if (tid == 0) is_last = atomicAdd(&arrivals[pid], 1u) == (unsigned)(splits - 1);
+        __syncthreads();
+        if (!is_last) return;
+        __threadfence();                       // see the other workgroups' slabs
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+        for (int sp = 0; sp < splits; ++sp) {
+            const float4* other = reinterpret_cast<const float4*>(slabs + ((size_t)sp * nblk + pid) * tile_elems);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 v = other[((a * TN + b) * 4 + q) * NT + tid];
+                        acc[a][b][4 * q] += v.x; acc[a][b][4 * q + 1] += v.y;
+                        acc[a][b][4 * q + 2] += v.z; acc[a][b][4 * q + 3] += v.w;
+                    }
         }
+        if (tid == 0) arrivals[pid] = 0u;      // ready for the next launch on this stream
     }
 
     const int rb0 = i0 + wm0, cb0 = j0 + wn0;
@@ -286,33 +341,49 @@ __global__ __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(B
 #undef CHIMERA_EPI
 }
 
-struct TileChoice { int bm, bn; };
+struct TileChoice { int bm, bn, splits; };
 
 TileChoice forced_tile() {
-    TileChoice c{0, 0};
-    const char* e = std::getenv("CHIMERA_GEMM_TILE");   // e.g. "256x128"; tuning aid
-    if (e) std::sscanf(e, "%dx%d", &c.bm, &c.bn);
+    TileChoice c{0, 0, 0};
+    const char* e = std::getenv("CHIMERA_GEMM_TILE");   // e.g. "256x256" or "256x256x4" (x splits); tuning aid
+    if (e) std::sscanf(e, "%dx%dx%d", &c.bm, &c.bn, &c.splits);
     return c;
 }
 
-// 256x256 (8 wavefronts) once it gives most of the 256 CUs a tile, else 128x128
-// (4 wavefronts, two workgroups per CU).  Thresholds from measurements on MI355X.
+constexpr int MAX_SPLITS = 8;
+
+// 256x256 (8 wavefronts) once the output has enough such tiles for most of the 256 CUs,
+// else 128x128 (4 wavefronts, two workgroups per CU); thresholds measured on MI355X.
+// A CU fills LDS from L2 at roughly 64 bytes per clock, so a 128x128x64 step (32 KiB for
+// 512 clocks of MFMA work) is fed at half the rate the matrix cores could use; 256x256
+// halves the bytes per flop, which is why it wins whenever it can occupy the chip.
+// Split-K (several workgroups per 256x256 tile, see the kernel) is available on request
+// (CHIMERA_GEMM_TILE=256x256x<splits> plus a workspace) but not chosen by default: on
+// MI355X the device-wide fences its hand-over needs cost more than the idle CUs.
 TileChoice choose_tile(const GemmArgs& g) {
-    const TileChoice f = forced_tile();
-    if (f.bm) return f;
+    TileChoice f = forced_tile();
     const long t256 = (long)((g.m + 255) / 256) * ((g.n + 255) / 256);
-    if (t256 >= 160) return {256, 256};
-    return {128, 128};
+    if (f.bm) {
+        if (f.splits < 1 || f.bm != 256) f.splits = 1;
+        f.splits = std::min(f.splits, std::min(MAX_SPLITS, std::max(1, (g.k + BK - 1) / BK)));
+        if (f.splits > 1 && (!g.ws || g.ws_bytes < gemm_mfma_workspace_bytes(g.m, g.n, f.splits))) f.splits = 1;
+        return f;
+    }
+    if (t256 >= 160) return {256, 256, 1};
+    return {128, 128, 1};
 }
 
 template <int BM, int BN, int WGM, int WGN, int PF>
-int launch_layout(const GemmArgs& g, hipStream_t s) {
+int launch_layout(const GemmArgs& g, int splits, hipStream_t s) {
     const int tm = (g.m + BM - 1) / BM, tn = (g.n + BN - 1) / BN;
-    const dim3 grid(tm * tn), block(WGM * WGN * 64);
+    const dim3 grid(tm * tn * splits), block(WGM * WGN * 64);
+    unsigned* arrivals = (unsigned*)g.ws;                               // [tiles], zero between launches
+    float* slabs = g.ws ? (float*)((char*)g.ws + SPLITK_COUNTER_BYTES) : nullptr;
 #define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                              \
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, PF, AKC, BKC>), grid, block, 0, s, (const bf16_t*)g.a,      \
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, PF, AKC, BKC>), grid, block, 0, s, (const bf16_t*)g.a,  \
                        (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c, (bf16_t*)g.c2, g.m, g.n, \
-                       g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf, (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn)
+                       g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf, (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn,    \
+                       splits, slabs, arrivals)
     if (g.a_kc && !g.b_kc) CHIMERA_GEMM_LAUNCH(true, false);
     else if (g.a_kc && g.b_kc) CHIMERA_GEMM_LAUNCH(true, true);
     else CHIMERA_GEMM_LAUNCH(false, false);
@@ -328,7 +399,22 @@ bool gemm_mfma_supports(const GemmArgs& g) {
     if ((g.k % 8) || (g.n % 8) || (g.lda % 8) || (g.ldb % 8)) return false;
     if (!g.a_kc && (g.m % 8)) return false;
     if (((uintptr_t)g.a | (uintptr_t)g.b) & 15) return false;  // 16-byte vector loads
+    // operand elements are addressed with 32-bit offsets
+    const unsigned long long ea = (unsigned long long)(g.a_kc ? g.m : g.k) * g.lda, eb = (unsigned long long)(g.b_kc ? g.n : g.k) * g.ldb;
+    if (ea >= (1ull << 32) || eb >= (1ull << 32)) return false;
     return g.m >= 1 && g.n >= 1 && g.k >= 1;
+}
+
+// Workspace of a split-K launch: arrival counters (zero before the first launch, left zero
+// by every launch) followed by one float slab per (split, 256x256 tile).
+size_t gemm_mfma_workspace_bytes(int m, int n, int splits) {
+    const size_t tiles = (size_t)((m + 255) / 256) * ((n + 255) / 256);
+    return SPLITK_COUNTER_BYTES + (size_t)splits * tiles * 256 * 256 * sizeof(float);
+}
+// Workspace that allows any split count up to MAX_SPLITS for an m x n output.
+size_t gemm_mfma_workspace_need(int m, int n, int k) {
+    if (m < 1 || n < 1 || k < 1) return 0;
+    return gemm_mfma_workspace_bytes(m, n, MAX_SPLITS);
 }
 
 int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
@@ -336,9 +422,10 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     if (g.epilogue < EPI_NONE || g.epilogue > EPI_ACCUM_F32) return fail(CHIMERA_EINVAL, "unknown epilogue %d", g.epilogue);
     hipStream_t s = (hipStream_t)stream;
     const TileChoice t = choose_tile(g);
-    if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4, 1>(g, s);
-    const char* pf = std::getenv("CHIMERA_GEMM_PF");
-    if (t.bm == 128 && t.bn == 128) return (pf && pf[0] == '2') ? launch_layout<128, 128, 2, 2, 2>(g, s) : launch_layout<128, 128, 2, 2, 1>(g, s);
+    if (t.splits > 1 && (size_t)((g.m + 255) / 256) * ((g.n + 255) / 256) * sizeof(unsigned) > SPLITK_COUNTER_BYTES)
+        return fail(CHIMERA_EINVAL, "too many tiles for split-K");
+    if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4, 1>(g, t.splits, s);
+    if (t.bm == 128 && t.bn == 128) return launch_layout<128, 128, 2, 2, 1>(g, 1, s);
     return fail(CHIMERA_EINVAL, "no %dx%d gemm tile", t.bm, t.bn);
 }
 

@@ -51,11 +51,15 @@ struct GemmArgs {
     void* c2;                           // [m,n]
     int epilogue;
     int gelu_erf;
+    void* ws;                           // optional split-K workspace (bf16 matrix-core path), may be null
+    size_t ws_bytes;
 };
 
 int gemm_reference(int dtype, const GemmArgs& g, void* stream);
 int gemm_mfma_bf16(const GemmArgs& g, void* stream);
 bool gemm_mfma_supports(const GemmArgs& g);
+size_t gemm_mfma_workspace_bytes(int m, int n, int splits);
+size_t gemm_mfma_workspace_need(int m, int n, int k);   // bytes the tile heuristic wants for this shape (0 = none)
 
 // x_f32 / res_f32: that operand is float although the stage dtype is bf16 (the
 // residual stream inside a bf16 stage is kept in float).  dx_lo (stage dtype) and

@@ -73,7 +73,7 @@ struct chimera_stage {
     int L, H, heads, S, B, dtype;
     int M, d;
     size_t esz;
-    int causal = 1, gelu_erf = 0, kernels = 0;
+    int causal = 1, gelu_erf = 0, kernels = 0, overlap = 1;
     bool bound = false;
 
     // parameter offsets (elements) inside one block and block size
@@ -85,7 +85,7 @@ struct chimera_stage {
     size_t layer_stash, slot_bytes;
 
     // workspace layout (bytes)
-    size_t w_dy[2], w_dyf[2], w_dx1f, w_du, w_dh, w_dx1, w_dctx, w_dqkv, w_delta, w_scratch, ws_bytes;
+    size_t w_dy[2], w_dyf[2], w_dx1f, w_du[2], w_dh, w_dx1[2], w_dctx, w_dqkv[2], w_delta, w_scratch, w_scratch2, ws_bytes;
 
     const char* weights = nullptr;
     float* grads = nullptr;
@@ -93,6 +93,14 @@ struct chimera_stage {
     char* ws = nullptr;
     int slots = 0;
     hipStream_t stream = nullptr;
+    // Weight and bias gradients run on a second stream beside the chain of input
+    // gradients: they are off the critical path of a backward and fill the CUs that
+    // the chain's smaller kernels leave idle.  Gradient buffers are only ever
+    // touched by that stream (or by the main one with the side stream idle).
+    hipStream_t side = nullptr;
+    hipEvent_t ev_ready[4] = {};      // main -> side: dy, du, dx1, dqkv of the current block are written
+    hipEvent_t ev_side[2] = {};       // side -> main: the side work of a block (by parity) is done
+    bool have_side = false;
 
     struct IO { const void* x; void* y; const void* dy; void* dx; };
     std::unordered_map<int, IO> io;
@@ -139,21 +147,22 @@ void layout(chimera_stage* st) {
     st->w_dy[0] = takeb(M * H * e); st->w_dy[1] = takeb(M * H * e);
     st->w_dyf[0] = takeb(M * H * 4); st->w_dyf[1] = takeb(M * H * 4);
     st->w_dx1f = takeb(M * H * 4);
-    st->w_du = takeb(M * 4 * H * e);
+    st->w_du[0] = takeb(M * 4 * H * e); st->w_du[1] = takeb(M * 4 * H * e);
     st->w_dh = takeb(M * H * e);
-    st->w_dx1 = takeb(M * H * e);
+    st->w_dx1[0] = takeb(M * H * e); st->w_dx1[1] = takeb(M * H * e);
     st->w_dctx = takeb(M * H * e);
-    st->w_dqkv = takeb(M * 3 * H * e);
+    st->w_dqkv[0] = takeb(M * 3 * H * e); st->w_dqkv[1] = takeb(M * 3 * H * e);
     st->w_delta = takeb((size_t)st->B * st->heads * st->S * 4);
     const size_t sc = std::max(colsum_scratch_floats((int)M, (int)(4 * H)), layernorm_bwd_scratch_floats((int)M, (int)H));
     st->w_scratch = takeb(sc * 4);
+    st->w_scratch2 = takeb(sc * 4);
     st->ws_bytes = b;
 }
 
-int gemm(chimera_stage* st, const GemmArgs& g, int cls) {
-    ProfScope prof(cls, 2.0 * g.m * g.n * g.k, st->stream);
-    if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_supports(g)) return gemm_mfma_bf16(g, st->stream);
-    return gemm_reference(st->dtype, g, st->stream);
+int gemm(chimera_stage* st, const GemmArgs& g, int cls, hipStream_t stream) {
+    ProfScope prof(cls, 2.0 * g.m * g.n * g.k, stream);
+    if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_supports(g)) return gemm_mfma_bf16(g, stream);
+    return gemm_reference(st->dtype, g, stream);
 }
 
 // C[m,n] = X[m,k] W[k,n] (+ epilogue); W stored [in, out].
@@ -165,7 +174,7 @@ int linear_fwd(chimera_stage* st, int m, int n, int k, const void* x, const void
     g.b = w; g.ldb = n; g.b_kc = 0;
     g.bias = bias; g.r = r; g.c = c; g.c2 = c2; g.epilogue = epi; g.gelu_erf = st->gelu_erf;
     g.r_f32 = r_f32; g.c_f32 = c_f32;
-    return gemm(st, g, PC_GEMM_FWD);
+    return gemm(st, g, PC_GEMM_FWD, st->stream);
 }
 // dX[m,k] = dY[m,n] W^T, W stored [k, n]: contraction over n, contiguous in both.
 int linear_dgrad(chimera_stage* st, int m, int n, int k, const void* dy, const void* w, const void* r, void* dx, int epi) {
@@ -174,16 +183,16 @@ int linear_dgrad(chimera_stage* st, int m, int n, int k, const void* dy, const v
     g.a = dy; g.lda = n; g.a_kc = 1;
     g.b = w; g.ldb = n; g.b_kc = 1;
     g.r = r; g.c = dx; g.epilogue = epi; g.gelu_erf = st->gelu_erf;
-    return gemm(st, g, PC_GEMM_DGRAD);
+    return gemm(st, g, PC_GEMM_DGRAD, st->stream);
 }
 // dW[k,n] += X[m,k]^T dY[m,n]: contraction over the tokens.
-int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const void* dy, float* dw) {
+int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const void* dy, float* dw, hipStream_t stream) {
     GemmArgs g{};
     g.m = k; g.n = n; g.k = m;
     g.a = x; g.lda = k; g.a_kc = 0;
     g.b = dy; g.ldb = n; g.b_kc = 0;
     g.c = dw; g.epilogue = EPI_ACCUM_F32;
-    return gemm(st, g, PC_GEMM_WGRAD);
+    return gemm(st, g, PC_GEMM_WGRAD, stream);
 }
 
 int attn_args(chimera_stage* st, AttnArgs& a) {
@@ -220,9 +229,19 @@ int st_ln_bwd(chimera_stage* st, const void* dy, const void* x, int x_f32, const
     return layernorm_bwd(st->dtype, st->M, st->H, dy, x, x_f32, mean, rstd, g, res, res_f32, dx_lo, dx_hi, dg, db, scratch,
                          st->stream);
 }
-int st_colsum(chimera_stage* st, int cols, const void* x, float* out, float* scratch) {
-    ProfScope prof(PC_COLSUM, (double)st->M * cols * st->esz, st->stream);
-    return colsum(st->dtype, st->M, cols, x, out, scratch, st->stream);
+int st_colsum(chimera_stage* st, int cols, const void* x, float* out, float* scratch, hipStream_t stream) {
+    ProfScope prof(PC_COLSUM, (double)st->M * cols * st->esz, stream);
+    return colsum(st->dtype, st->M, cols, x, out, scratch, stream);
+}
+
+#define HIP_TRY(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return fail(CHIMERA_EDEVICE, "%s: %s", #expr, hipGetErrorString(e__)); } while (0)
+
+// side stream waits until the main stream has reached this point
+int fork_to_side(chimera_stage* st, int which) {
+    if (!st->have_side) return CHIMERA_OK;
+    HIP_TRY(hipEventRecord(st->ev_ready[which], st->stream));
+    HIP_TRY(hipStreamWaitEvent(st->side, st->ev_ready[which], 0));
+    return CHIMERA_OK;
 }
 
 // Inside a bf16 stage the residual stream (x -> x1 -> y of every block) stays in
@@ -267,20 +286,27 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
     const int M = st->M, H = st->H, L = st->L;
     const int wide = st->dtype == CHIMERA_BF16;
     float* scratch = (float*)(st->ws + st->w_scratch);
-    void* du = st->ws + st->w_du;
+    float* scratch2 = (float*)(st->ws + (st->have_side ? st->w_scratch2 : st->w_scratch));
+    hipStream_t gs = st->have_side ? st->side : st->stream;       // stream of the parameter gradients
     void* dh = st->ws + st->w_dh;
-    void* dx1 = st->ws + st->w_dx1;
     float* dx1f = wide ? (float*)(st->ws + st->w_dx1f) : nullptr;
     void* dctx = st->ws + st->w_dctx;
-    void* dqkv = st->ws + st->w_dqkv;
     const void* dy = io.dy;           // stage dtype: operand of the products
     const void* dyr = io.dy;          // what the residual path adds (float inside a bf16 stage)
     int dyr_f32 = 0;
     for (int l = L - 1; l >= 0; --l) {
+        const int par = l & 1;
+        // du, dx1, dqkv and the dy ping-pong alternate between two buffers by block parity, so
+        // before this block overwrites a buffer the side stream must be done with the block
+        // two above, which read it
+        if (st->have_side && l + 2 <= L - 1) HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_side[par], 0));
+        void* du = st->ws + st->w_du[par];
+        void* dx1 = st->ws + st->w_dx1[par];
+        void* dqkv = st->ws + st->w_dqkv[par];
         const void* x = l == 0 ? io.x : st->ST(slot, l - 1, st->s_y);
         const int x_f32 = wide && l > 0;
-        void* dx = l == 0 ? io.dx : (void*)(st->ws + st->w_dy[l & 1]);
-        float* dxf = (wide && l > 0) ? (float*)(st->ws + st->w_dyf[l & 1]) : nullptr;
+        void* dx = l == 0 ? io.dx : (void*)(st->ws + st->w_dy[par]);
+        float* dxf = (wide && l > 0) ? (float*)(st->ws + st->w_dyf[par]) : nullptr;
         const void* h1 = st->ST(slot, l, st->s_h1);
         const void* qkv = st->ST(slot, l, st->s_qkv);
         const void* ctx = st->ST(slot, l, st->s_ctx);
@@ -289,18 +315,21 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         const void* u = st->ST(slot, l, st->s_u);
         const void* g = st->ST(slot, l, st->s_g);
         // y = x1 + g W2 + b2
-        TRY(st_colsum(st, H, dy, st->G(l, st->o_b_fc2), scratch));
-        TRY(linear_wgrad(st, M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2)));
+        TRY(fork_to_side(st, 0));
+        TRY(st_colsum(st, H, dy, st->G(l, st->o_b_fc2), scratch2, gs));
+        TRY(linear_wgrad(st, M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2), gs));
         TRY(linear_dgrad(st, M, H, 4 * H, dy, st->W(l, st->o_w_fc2), u, du, EPI_DGELU));       // du = dg * GeLU'(u)
         // u = h2 W1 + b1
-        TRY(st_colsum(st, 4 * H, du, st->G(l, st->o_b_fc1), scratch));
-        TRY(linear_wgrad(st, M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1)));
+        TRY(fork_to_side(st, 1));
+        TRY(st_colsum(st, 4 * H, du, st->G(l, st->o_b_fc1), scratch2, gs));
+        TRY(linear_wgrad(st, M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1), gs));
         TRY(linear_dgrad(st, M, 4 * H, H, du, st->W(l, st->o_w_fc1), nullptr, dh, EPI_NONE));
         TRY(st_ln_bwd(st, dh, x1, wide, (const float*)st->ST(slot, l, st->s_mean2), (const float*)st->ST(slot, l, st->s_rstd2),
                       st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch));
         // x1 = x + ctx Wo + bo
-        TRY(st_colsum(st, H, dx1, st->G(l, st->o_b_o), scratch));
-        TRY(linear_wgrad(st, M, H, H, ctx, dx1, st->G(l, st->o_w_o)));
+        TRY(fork_to_side(st, 2));
+        TRY(st_colsum(st, H, dx1, st->G(l, st->o_b_o), scratch2, gs));
+        TRY(linear_wgrad(st, M, H, H, ctx, dx1, st->G(l, st->o_w_o), gs));
         TRY(linear_dgrad(st, M, H, H, dx1, st->W(l, st->o_w_o), nullptr, dctx, EPI_NONE));
         AttnArgs a{};
         attn_args(st, a);
@@ -308,15 +337,25 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         a.dctx = dctx; a.dqkv = dqkv; a.delta = (float*)(st->ws + st->w_delta);
         TRY(st_attn_bwd(st, a));
         // qkv = h1 Wqkv + bqkv
-        TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch));
-        TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv)));
+        TRY(fork_to_side(st, 3));
+        TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch2, gs));
+        TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv), gs));
+        if (st->have_side) HIP_TRY(hipEventRecord(st->ev_side[par], st->side));
         TRY(linear_dgrad(st, M, 3 * H, H, dqkv, st->W(l, st->o_w_qkv), nullptr, dh, EPI_NONE));
+        // dx goes into the buffer that the block above read its dy from, also on the side stream
+        if (st->have_side && l + 1 <= L - 1) HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_side[(l + 1) & 1], 0));
         TRY(st_ln_bwd(st, dh, x, x_f32, (const float*)st->ST(slot, l, st->s_mean1), (const float*)st->ST(slot, l, st->s_rstd1),
                       st->W(l, st->o_ln1_g), wide ? (const void*)dx1f : (const void*)dx1, wide, dx, dxf,
                       st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch));
         dy = dx;
         dyr = dxf ? (const void*)dxf : (const void*)dx;
         dyr_f32 = dxf != nullptr;
+    }
+    // the stash slot, the workspace and the gradient buffers are free for the next op only
+    // once the side stream has drained
+    if (st->have_side) {
+        HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_side[0], 0));
+        if (L > 1) HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_side[1], 0));
     }
     return CHIMERA_OK;
 }
@@ -361,14 +400,26 @@ int chimera_stage_set_option(chimera_stage* st, int key, int value) {
         case CHIMERA_OPT_CAUSAL: if (value != 0 && value != 1) break; st->causal = value; return CHIMERA_OK;
         case CHIMERA_OPT_GELU: if (value != 0 && value != 1) break; st->gelu_erf = value; return CHIMERA_OK;
         case CHIMERA_OPT_KERNELS: if (value != 0 && value != 1) break; st->kernels = value; return CHIMERA_OK;
+        case CHIMERA_OPT_OVERLAP: if (value != 0 && value != 1) break; st->overlap = value; return CHIMERA_OK;
         default: return fail(CHIMERA_EINVAL, "unknown option %d", key);
     }
     return fail(CHIMERA_EINVAL, "bad value %d for option %d", value, key);
 }
 
+static void drop_side(chimera_stage* st) {
+    if (!st->have_side) return;
+    (void)hipStreamSynchronize(st->side);
+    for (hipEvent_t& e : st->ev_ready) (void)hipEventDestroy(e);
+    for (hipEvent_t& e : st->ev_side) (void)hipEventDestroy(e);
+    (void)hipStreamDestroy(st->side);
+    st->have_side = false;
+}
+
 void chimera_stage_destroy(chimera_stage* st) {
+    if (!st) return;
     if (g_worker.down == st) g_worker.down = nullptr;
     if (g_worker.up == st) g_worker.up = nullptr;
+    drop_side(st);
     delete st;
 }
 
@@ -388,6 +439,17 @@ int chimera_stage_bind(chimera_stage* st, const void* d_weights, float* d_grads,
     st->weights = (const char*)d_weights; st->grads = d_grads; st->stash = (char*)d_stash; st->ws = (char*)d_workspace;
     st->slots = stash_slots; st->stream = (hipStream_t)hip_stream;
     st->slot_used.assign(stash_slots, 0);
+    drop_side(st);
+    if (st->overlap) {
+        // default priority on purpose; non-blocking so that it never syncs with the NULL stream implicitly
+        if (hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking) != hipSuccess)
+            return fail(CHIMERA_EDEVICE, "cannot create the side stream");
+        bool ok = true;
+        for (hipEvent_t& e : st->ev_ready) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+        for (hipEvent_t& e : st->ev_side) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+        if (!ok) return fail(CHIMERA_EDEVICE, "cannot create events");
+        st->have_side = true;
+    }
     st->bound = true;
     return CHIMERA_OK;
 }
@@ -555,7 +617,7 @@ int chimera_profile_read(int cls, double* h_ms, long long* h_launches, double* h
 // ------------------------------------------------------------ single operators
 int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int n, int k, const void* d_a, int lda,
                     int a_kc, const void* d_b, int ldb, int b_kc, const void* d_bias, const void* d_r, void* d_c,
-                    void* d_c2, void* hip_stream) {
+                    void* d_c2, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
     if (!d_a || !d_b || !d_c) return fail(CHIMERA_EINVAL, "NULL operand");
     if (m < 1 || n < 1 || k < 1) return fail(CHIMERA_EINVAL, "gemm sizes must be positive");
     if ((k % 8) || (n % 8) || (lda % 8) || (ldb % 8)) return fail(CHIMERA_EINVAL, "k, n, lda, ldb must be multiples of 8");
@@ -569,9 +631,12 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int
     GemmArgs g{};
     g.m = m; g.n = n; g.k = k; g.a = d_a; g.lda = lda; g.a_kc = a_kc ? 1 : 0; g.b = d_b; g.ldb = ldb; g.b_kc = b_kc ? 1 : 0;
     g.bias = d_bias; g.r = d_r; g.c = d_c; g.c2 = d_c2; g.epilogue = epilogue; g.gelu_erf = gelu_kind ? 1 : 0;
+    g.ws = d_workspace; g.ws_bytes = d_workspace ? workspace_bytes : 0;
     if (impl == 0 && dtype == CHIMERA_BF16 && gemm_mfma_supports(g)) return gemm_mfma_bf16(g, hip_stream);
     return gemm_reference(dtype, g, hip_stream);
 }
+
+size_t chimera_op_gemm_workspace_bytes(int m, int n, int k) { return gemm_mfma_workspace_need(m, n, k); }
 
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x, const void* d_gamma, const void* d_beta,
                              void* d_y, float* d_mean, float* d_rstd, void* hip_stream) {

@@ -19,7 +19,8 @@ def _rand(shape, seed, dtype, scale=1.0):
     return synth.round_to_bf16(a) if dtype == b.BF16 else a
 
 
-GEMM_SHAPES = [(128, 384, 128), (200, 136, 72), (512, 512, 256), (304, 1600, 320), (1024, 264, 1032), (8, 8, 8)]
+GEMM_SHAPES = [(128, 384, 128), (200, 136, 72), (512, 512, 256), (304, 1600, 320), (1024, 264, 1032), (8, 8, 8),
+               (512, 520, 2048)]
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -72,6 +73,35 @@ def test_gemm_epilogues(dtype, impl, gelu_erf):
     assert_close(to_np(c), acc + bias + R, dtype, "bias+residual")
     b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_DGELU, r=dr, impl=impl, gelu_erf=gelu_erf)
     assert_close(to_np(c), acc * bo.gelu_grad(R.astype(np.float64), kind), dtype, "dgelu")
+
+
+def test_gemm_split_k_matches_unsplit_and_is_reproducible():
+    """On request (tile override plus a workspace) the bf16 kernel splits k over several
+    workgroups per tile; partial sums are added in a fixed order, so two runs agree bit
+    for bit, and the result matches the oracle like the unsplit one."""
+    import os
+    import torch
+    m, n, k = 1024, 1024, 4096
+    assert b.lib().chimera_op_gemm_workspace_bytes(m, n, k) > 0
+    os.environ["CHIMERA_GEMM_TILE"] = "256x256x4"
+    A, B = _rand((m, k), 1, b.BF16), _rand((k, n), 2, b.BF16)
+    want = A.astype(np.float64) @ B.astype(np.float64)
+    da, db = to_dev(A, b.BF16), to_dev(B, b.BF16)
+    outs = []
+    for ws in ("auto", "auto", None):
+        c = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+        b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, workspace=ws)
+        torch.cuda.synchronize()
+        assert_close(to_np(c), want, b.BF16)
+        outs.append(c)
+    assert torch.equal(outs[0], outs[1])
+    # accumulate epilogue through the split path, twice
+    dw = torch.zeros((m, n), device="cuda")
+    at = to_dev(np.ascontiguousarray(A.T), b.BF16)
+    for _ in range(2):
+        b.chimera_op_gemm(at, db, dw, m, n, k, 0, 0, b.EPI_ACCUM_F32)
+    assert_close(to_np(dw), 2 * want, b.BF16)
+    del os.environ["CHIMERA_GEMM_TILE"]
 
 
 def test_gemm_argument_errors():
