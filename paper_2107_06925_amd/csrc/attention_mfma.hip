@@ -133,6 +133,26 @@ __device__ __forceinline__ void store_trans(const TransRegs<D>& r, bf16_t* lds, 
     }
 }
 
+// One 64 x D global block kept BOTH ways (straight in `lds_s`, transposed in `lds_t`) from a
+// single set of loads: a thread's unit of 4 rows x 8 columns is four straight 16-byte
+// chunks as loaded, and four 8-byte transposed pieces after the register shuffle.
+template <int D>
+__device__ __forceinline__ void store_both(const TransRegs<D>& r, bf16_t* lds_s, bf16_t* lds_t, int tid) {
+    constexpr int IG = D / 8;
+#pragma unroll
+    for (int it = 0; it < TransRegs<D>::UPT; ++it) {
+        const int u = tid + it * NT;
+        if (u >= TransRegs<D>::UNITS) continue;
+        const int ig = u % IG, kg = u / IG;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const int row = kg * 4 + rr;
+            *reinterpret_cast<uint4*>(lds_s + (ig >> 3) * 4096 + tile_off(row, ig & 7)) = r.v[it * 4 + rr];
+        }
+    }
+    store_trans<D>(r, lds_t, tid);
+}
+
 // Operand fragment of a straight tile: row `row` (0..63), contraction step kk (16 columns each).
 template <int D>
 __device__ __forceinline__ bf16x8 frag_straight(const bf16_t* lds, int row, int kk, int g) {
@@ -302,10 +322,14 @@ __global__ __launch_bounds__(NT) void attn_delta_kernel(const bf16_t* __restrict
 // dK, dV of 128 keys (32 per wavefront), looping over 64-query tiles.
 //   S  = Q K^T (queries x keys)   P = exp2(S c - lse2)     dP = dO V^T
 //   dS = P (dP - delta)           dV^T += dO^T P           dK^T += Q^T dS (then * 1/sqrt(d))
+// The next tile's Q, dO, lse and delta are already on their way to registers while the
+// matrix cores work on the current one; each 32-query half of a tile is finished (scores
+// to dK/dV) before the next starts, which keeps the live score registers at 32.
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                          bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2)))
+void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                         const float* __restrict__ lse, const float* __restrict__ delta,
+                         bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
     __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * D], Qt[64 * D], Os[64 * D], Ot[64 * D];
     __shared__ __attribute__((aligned(16))) float lse2[64], dl[64];
@@ -332,36 +356,38 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restri
 
     const int qt0 = CAUSAL ? j0 / 64 : 0;
     const int ntiles = (S + 63) / 64;
+    TransRegs<D> rq, ro;
+    float stat = 0.f;                      // lse (threads 0..63) or delta (threads 64..127) of the next tile
+    auto fetch = [&](int t) {
+        const int i0 = t * 64;
+        load_trans<D>(rq, base, ld, i0, S, tid);
+        load_trans<D>(ro, dOg, H, i0, S, tid);
+        if (tid < 128) {
+            const int i = i0 + (tid & 63);
+            stat = i < S ? (tid < 64 ? lse[stat0 + i] * LOG2E : delta[stat0 + i]) : 0.f;
+        }
+    };
+    fetch(qt0);
     for (int t = qt0; t < ntiles; ++t) {
         const int i0 = t * 64;
-        StraightRegs<D> rs_;
-        TransRegs<D> rt_;
-        load_straight<D>(rs_, base, ld, i0, S, tid);
-        load_trans<D>(rt_, base, ld, i0, S, tid);
-        store_straight<D>(rs_, Qs, tid);
-        store_trans<D>(rt_, Qt, tid);
-        load_straight<D>(rs_, dOg, H, i0, S, tid);
-        load_trans<D>(rt_, dOg, H, i0, S, tid);
-        store_straight<D>(rs_, Os, tid);
-        store_trans<D>(rt_, Ot, tid);
-        if (tid < 64) {
-            const int i = i0 + tid;
-            lse2[tid] = i < S ? lse[stat0 + i] * LOG2E : 0.f;
-            dl[tid] = i < S ? delta[stat0 + i] : 0.f;
-        }
+        store_both<D>(rq, Qs, Qt, tid);
+        store_both<D>(ro, Os, Ot, tid);
+        if (tid < 64) lse2[tid] = stat;
+        else if (tid < 128) dl[tid - 64] = stat;
         __syncthreads();
+        if (t + 1 < ntiles) fetch(t + 1);
         const bool live = !CAUSAL || i0 + 63 >= wj0;           // some query of the tile sees some key of this wavefront
         if (live) {
             const bool edge = (i0 + 63 >= S) || (CAUSAL && i0 < wj0 + 31);
-            f32x16 p[2], dp[2];
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
+                f32x16 p, dp;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { p[it][r] = 0.f; dp[it][r] = 0.f; }
+                for (int r = 0; r < 16; ++r) { p[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk) {
-                    p[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Qs, it * 32 + l32, kk, g), kf[kk], p[it], 0, 0, 0);
-                    dp[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Os, it * 32 + l32, kk, g), vf[kk], dp[it], 0, 0, 0);
+                    p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Qs, it * 32 + l32, kk, g), kf[kk], p, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Os, it * 32 + l32, kk, g), vf[kk], dp, 0, 0, 0);
                 }
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
@@ -372,24 +398,25 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restri
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const int r = r4 * 4 + c;
-                        float pv = exp2f(p[it][r] * c2 - lv[c]);
+                        float pv = exp2f(p[r] * c2 - lv[c]);
                         if (edge) {
                             const int i = i0 + il + c;
                             if (i >= S || (CAUSAL && i < jrow)) pv = 0.f;
                         }
-                        p[it][r] = pv;
-                        dp[it][r] = pv * (dp[it][r] - dv4[c]);
+                        p[r] = pv;
+                        dp[r] = pv * (dp[r] - dv4[c]);
                     }
                 }
-            }
 #pragma unroll
-            for (int J = 0; J < 4; ++J) {
-                const bf16x8 pf = pack8(p[J >> 1], (J & 1) * 8);
-                const bf16x8 dsf = pack8(dp[J >> 1], (J & 1) * 8);
+                for (int j = 0; j < 2; ++j) {
+                    const int J = it * 2 + j;
+                    const bf16x8 pf = pack8(p, j * 8);
+                    const bf16x8 dsf = pack8(dp, j * 8);
 #pragma unroll
-                for (int t2 = 0; t2 < OT; ++t2) {
-                    dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Ot, t2 * 32 + l32, J, g), pf, dv[t2], 0, 0, 0);
-                    dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Qt, t2 * 32 + l32, J, g), dsf, dk[t2], 0, 0, 0);
+                    for (int t2 = 0; t2 < OT; ++t2) {
+                        dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Ot, t2 * 32 + l32, J, g), pf, dv[t2], 0, 0, 0);
+                        dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Qt, t2 * 32 + l32, J, g), dsf, dk[t2], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -414,9 +441,10 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restri
 //   S^T = K Q^T (keys x queries)   P = exp2(S^T c - lse2)   dP^T = V dO^T
 //   dS^T = P (dP^T - delta)        dQ^T += K^T dS^T (then * 1/sqrt(d))
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                         const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2)))
+void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                        const float* __restrict__ lse, const float* __restrict__ delta,
+                        bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * D], Kt[64 * D], Vs[64 * D];
     const int H = heads * D, ld = 3 * H;
@@ -444,46 +472,48 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restric
 
     const int kv_end = CAUSAL ? min(S, q0 + 128) : S;
     const int ntiles = (kv_end + 63) / 64;
+    TransRegs<D> rk;
+    StraightRegs<D> rv;
+    auto fetch = [&](int t) {
+        load_trans<D>(rk, base + H, ld, t * 64, S, tid);
+        load_straight<D>(rv, base + 2 * H, ld, t * 64, S, tid);
+    };
+    fetch(0);
     for (int t = 0; t < ntiles; ++t) {
         const int k0 = t * 64;
-        StraightRegs<D> rs_;
-        TransRegs<D> rt_;
-        load_straight<D>(rs_, base + H, ld, k0, S, tid);
-        load_trans<D>(rt_, base + H, ld, k0, S, tid);
-        store_straight<D>(rs_, Ks, tid);
-        store_trans<D>(rt_, Kt, tid);
-        load_straight<D>(rs_, base + 2 * H, ld, k0, S, tid);
-        store_straight<D>(rs_, Vs, tid);
+        store_both<D>(rk, Ks, Kt, tid);
+        store_straight<D>(rv, Vs, tid);
         __syncthreads();
+        if (t + 1 < ntiles) fetch(t + 1);
         const bool live = !CAUSAL || k0 <= wq0 + 31;
         if (live) {
             const bool edge = (k0 + 63 >= S) || (CAUSAL && k0 + 63 > wq0);
-            f32x16 p[2], dp[2];
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
+                f32x16 p, dp;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { p[kt][r] = 0.f; dp[kt][r] = 0.f; }
+                for (int r = 0; r < 16; ++r) { p[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk) {
-                    p[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Ks, kt * 32 + l32, kk, g), qf[kk], p[kt], 0, 0, 0);
-                    dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Vs, kt * 32 + l32, kk, g), of[kk], dp[kt], 0, 0, 0);
+                    p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Ks, kt * 32 + l32, kk, g), qf[kk], p, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Vs, kt * 32 + l32, kk, g), of[kk], dp, 0, 0, 0);
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float pv = exp2f(p[kt][r] * c2 - my_lse2);
+                    float pv = exp2f(p[r] * c2 - my_lse2);
                     if (edge) {
                         const int key = k0 + kt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
                         if (key >= S || (CAUSAL && key > qrow)) pv = 0.f;
                     }
-                    dp[kt][r] = pv * (dp[kt][r] - my_dl);
+                    dp[r] = pv * (dp[r] - my_dl);
                 }
-            }
 #pragma unroll
-            for (int J = 0; J < 4; ++J) {
-                const bf16x8 dsf = pack8(dp[J >> 1], (J & 1) * 8);
+                for (int j = 0; j < 2; ++j) {
+                    const bf16x8 dsf = pack8(dp, j * 8);
 #pragma unroll
-                for (int t2 = 0; t2 < OT; ++t2)
-                    dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Kt, t2 * 32 + l32, J, g), dsf, dq[t2], 0, 0, 0);
+                    for (int t2 = 0; t2 < OT; ++t2)
+                        dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Kt, t2 * 32 + l32, kt * 2 + j, g), dsf, dq[t2], 0, 0, 0);
+                }
             }
         }
         __syncthreads();

@@ -11,18 +11,21 @@
 // loads of the next k step are already in flight to registers and are written
 // to buffer b^1 afterwards, one barrier per step.
 //
-// LDS always holds both operands as [row][k] with k contiguous (128 bytes per
-// row = 8 chunks of 16 bytes), which is the order the MFMA operand registers
-// want: lane l of a wavefront feeds row l%32 with the 8 consecutive k values
-// of chunk 2*kk + l/32.  An operand that is k-contiguous in memory is copied
-// chunk by chunk.  An operand whose OTHER index is contiguous in memory (W in
-// the forward, both operands in wgrad) is read in coalesced 16-byte pieces
-// along that index for 8 (or 4) consecutive k, transposed inside the thread's
-// registers, and written as k-contiguous pieces, so no transposed copy of any
-// activation or weight ever exists in HBM.
-// Chunk c of row r is stored at position c ^ (r & 7) ^ ((r >> 3) & 7): rows
-// r..r+7 of one logical chunk (an MFMA operand read) and rows r, r+8, ...,
-// r+56 (a transposed write) both fall on 8 different bank groups.
+// An operand that is k-contiguous in memory (X in the forward, both operands of
+// dgrad) sits in LDS as [row][k], 128 bytes per row, and lane l reads its MFMA
+// operand - row l%32, the 8 consecutive k of chunk 2*kk + l/32 - with one
+// 16-byte load.  Chunk c of row r is stored at c ^ (r & 7) ^ ((r >> 3) & 7), so the
+// 8 rows a read touches per bank cycle fall on 8 different bank groups.
+// An operand whose OTHER index is contiguous in memory (W in the forward, both
+// operands of wgrad) is copied to LDS as it lies in memory, [k][row], and the
+// transposition is done by the LDS hardware: ds_read_b64_tr_b16 hands lane i of
+// each 16-lane group the i-th 16-bit element of the data addressed by lanes
+// 4e + i/4 (e = 0..3), i.e. column i of a 4 x 16 block - four consecutive k of one
+// row.  Two such reads give the same 8 k values the other flavour gets from one
+// 16-byte load.  The 32-byte column blocks of row k are stored at block ^ (k & 3)
+// so that the four rows of a transposing read use all 32 banks.  No transposed
+// copy of any activation or weight exists in HBM, and no data is shuffled in
+// registers.
 //
 // Workgroups are renumbered so that each of the 8 XCDs (own L2 each; the
 // hardware deals consecutive workgroup ids round-robin over them) works on a
@@ -46,19 +49,15 @@ constexpr size_t SPLITK_COUNTER_BYTES = 4096;
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
 
-__device__ __forceinline__ unsigned half_of(const uint4& q, int t) {
-    const unsigned w = (t >> 1) == 0 ? q.x : (t >> 1) == 1 ? q.y : (t >> 1) == 2 ? q.z : q.w;
-    return (t & 1) ? (w >> 16) : (w & 0xffffu);
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+
+// LDS element offset of the 16-byte chunk `ic` (8 rows) of k-row `k` in a [BK][ROWS] tile
+template <int ROWS> __device__ __forceinline__ int mc_off(int k, int ic) {
+    return k * ROWS + (((ic >> 1) ^ (k & 3)) << 4) + ((ic & 1) << 3);
 }
 
-// k rows per transposing unit: 8 when every thread then still has a unit, else 4
-template <int ROWS, int NT> struct McShape {
-    static constexpr int KB = (ROWS * BK / 64 >= NT) ? 8 : 4;
-    static constexpr int UNITS = ROWS * BK / (8 * KB);      // 8 x KB element blocks in the tile
-    static constexpr int UPT = (UNITS + NT - 1) / NT;       // units per thread (threads beyond UNITS idle)
-};
 template <int ROWS, int NT, bool KC> struct Staged {
-    static constexpr int N = KC ? ROWS * (BK / 8) / NT : McShape<ROWS, NT>::UPT * McShape<ROWS, NT>::KB;
+    static constexpr int N = ROWS * (BK / 8) / NT;     // 16-byte chunks per thread
     uint4 v[N];
     unsigned ok;     // bit i: v[i] lies inside the matrix (others are zeroed when written to LDS)
 };
@@ -66,38 +65,28 @@ template <int ROWS, int NT, bool KC> struct Staged {
 // global -> registers for one operand tile of ROWS rows x BK k values.
 // KC: element (row, k) at base[row * ld + k].  !KC: at base[k * ld + row].
 // Loads are unconditional (an out-of-range piece reads element 0 instead and is
-// zeroed later), so no branch separates the loads of different k steps and they
-// can stay in flight across steps.
+// zeroed later), so no branch separates the loads of different k steps.
 template <int ROWS, int NT, bool KC>
 __device__ __forceinline__ void load_tile(Staged<ROWS, NT, KC>& st, const bf16_t* __restrict__ base, int ld, int row0,
                                           int nrows, int k0, int K, int tid) {
+    constexpr int CPT = ROWS * (BK / 8) / NT;
     unsigned okm = 0;
-    if constexpr (KC) {
-        constexpr int CPT = ROWS * (BK / 8) / NT;
 #pragma unroll
-        for (int it = 0; it < CPT; ++it) {
-            const int c = tid + it * NT;
+    for (int it = 0; it < CPT; ++it) {
+        const int c = tid + it * NT;
+        bool ok;
+        unsigned off;
+        if constexpr (KC) {
             const int gr = row0 + (c >> 3), gk = k0 + (c & 7) * 8;
-            const bool ok = gr < nrows && gk < K;
-            const unsigned off = ok ? (unsigned)gr * (unsigned)ld + (unsigned)gk : 0u;
-            st.v[it] = *reinterpret_cast<const uint4*>(base + off);
-            okm |= (ok ? 1u : 0u) << it;
+            ok = gr < nrows && gk < K;
+            off = (unsigned)gr * (unsigned)ld + (unsigned)gk;
+        } else {
+            const int gk = k0 + c / (ROWS / 8), gi = row0 + (c % (ROWS / 8)) * 8;
+            ok = gk < K && gi < nrows;
+            off = (unsigned)gk * (unsigned)ld + (unsigned)gi;
         }
-    } else {
-        constexpr int KB = McShape<ROWS, NT>::KB, UPT = McShape<ROWS, NT>::UPT, IG = ROWS / 8;
-#pragma unroll
-        for (int it = 0; it < UPT; ++it) {
-            const int u = tid + it * NT;
-            const int gi = row0 + (u % IG) * 8, kb = k0 + (u / IG) * KB;
-            const bool mine = (McShape<ROWS, NT>::UNITS % NT == 0 || u < McShape<ROWS, NT>::UNITS) && gi < nrows;
-#pragma unroll
-            for (int r = 0; r < KB; ++r) {
-                const bool ok = mine && kb + r < K;
-                const unsigned off = ok ? (unsigned)(kb + r) * (unsigned)ld + (unsigned)gi : 0u;
-                st.v[it * KB + r] = *reinterpret_cast<const uint4*>(base + off);
-                okm |= (ok ? 1u : 0u) << (it * KB + r);
-            }
-        }
+        st.v[it] = *reinterpret_cast<const uint4*>(base + (ok ? off : 0u));
+        okm |= (ok ? 1u : 0u) << it;
     }
     st.ok = okm;
 }
@@ -107,39 +96,35 @@ __device__ __forceinline__ uint4 keep_if(const uint4& q, unsigned mask, int bit)
     return make_uint4(ok ? q.x : 0u, ok ? q.y : 0u, ok ? q.z : 0u, ok ? q.w : 0u);
 }
 
-// registers -> LDS tile [ROWS][BK], swizzled.
+// registers -> LDS: [ROWS][BK] (KC) or [BK][ROWS] (!KC), swizzled as described above.
 template <int ROWS, int NT, bool KC>
 __device__ __forceinline__ void store_tile(const Staged<ROWS, NT, KC>& st, bf16_t* lds, int tid) {
+    constexpr int CPT = ROWS * (BK / 8) / NT;
+#pragma unroll
+    for (int it = 0; it < CPT; ++it) {
+        const int c = tid + it * NT;
+        int off;
+        if constexpr (KC) { const int row = c >> 3, kc = c & 7; off = row * BK + swz(row, kc) * 8; }
+        else off = mc_off<ROWS>(c / (ROWS / 8), c % (ROWS / 8));
+        *reinterpret_cast<uint4*>(lds + off) = keep_if(st.v[it], st.ok, it);
+    }
+}
+
+// MFMA operand of lane `lane` for the 32 rows starting at r0 and the 16 k values of step kk.
+template <int ROWS, bool KC>
+__device__ __forceinline__ bf16x8 read_frag(const bf16_t* lds, int r0, int kk, int lane) {
     if constexpr (KC) {
-        constexpr int CPT = ROWS * (BK / 8) / NT;
-#pragma unroll
-        for (int it = 0; it < CPT; ++it) {
-            const int c = tid + it * NT;
-            const int row = c >> 3, kc = c & 7;
-            *reinterpret_cast<uint4*>(lds + row * BK + swz(row, kc) * 8) = keep_if(st.v[it], st.ok, it);
-        }
+        const int row = r0 + (lane & 31);
+        return *reinterpret_cast<const bf16x8*>(lds + row * BK + swz(row, kk * 2 + (lane >> 5)) * 8);
     } else {
-        constexpr int KB = McShape<ROWS, NT>::KB, UPT = McShape<ROWS, NT>::UPT, IG = ROWS / 8;
-#pragma unroll
-        for (int it = 0; it < UPT; ++it) {
-            const int u = tid + it * NT;
-            if (McShape<ROWS, NT>::UNITS % NT != 0 && u >= McShape<ROWS, NT>::UNITS) continue;
-            const int ig = u % IG, kg = u / IG;
-            const int chunk = (kg * KB) >> 3, within = (kg * KB) & 7;
-            uint4 q[KB];
-#pragma unroll
-            for (int r = 0; r < KB; ++r) q[r] = keep_if(st.v[it * KB + r], st.ok, it * KB + r);
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const int row = ig * 8 + t;
-                bf16_t* dst = lds + row * BK + swz(row, chunk) * 8 + within;
-                unsigned w[KB / 2];
-#pragma unroll
-                for (int p = 0; p < KB / 2; ++p) w[p] = half_of(q[2 * p], t) | (half_of(q[2 * p + 1], t) << 16);
-                if constexpr (KB == 8) *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
-                else *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
-            }
-        }
+        const int i = lane & 15, blk = (r0 >> 4) + ((lane >> 4) & 1);      // 16-row column block of this lane group
+        const int k = kk * 16 + (lane >> 5) * 8 + (i >> 2);                // row this lane addresses (first read)
+        typedef bf16x4 __attribute__((address_space(3))) * lds_v4;
+        const bf16_t* p0 = lds + k * ROWS + ((blk ^ (k & 3)) << 4) + ((i & 3) << 2);
+        const bf16_t* p1 = lds + (k + 4) * ROWS + ((blk ^ ((k + 4) & 3)) << 4) + ((i & 3) << 2);
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p0);
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p1);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
 }
 
@@ -228,15 +213,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[TM], bfr[TN];
 #pragma unroll
-            for (int a = 0; a < TM; ++a) {
-                const int row = wm0 + a * 32 + l32;
-                af[a] = *reinterpret_cast<const bf16x8*>(As + row * BK + swz(row, kk * 2 + lhi) * 8);
-            }
+            for (int a = 0; a < TM; ++a) af[a] = read_frag<BM, A_KC>(As, wm0 + a * 32, kk, lane);
 #pragma unroll
-            for (int b = 0; b < TN; ++b) {
-                const int row = wn0 + b * 32 + l32;
-                bfr[b] = *reinterpret_cast<const bf16x8*>(Bs + row * BK + swz(row, kk * 2 + lhi) * 8);
-            }
+            for (int b = 0; b < TN; ++b) bfr[b] = read_frag<BN, B_KC>(Bs, wn0 + b * 32, kk, lane);
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -341,6 +320,143 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
 #undef CHIMERA_EPI
 }
 
+// ---------------------------------------------------------------- async variant
+// Same tiles, same LDS layouts, same MFMA loop, but the tiles travel global -> LDS
+// without passing through registers (global_load_lds_dwordx4: lane i of a wavefront
+// writes 16 bytes at LDS base + 16 i), into a ring of NS stages, so the loads of the
+// next NS-1 k steps are in flight while the matrix cores work.  Because the LDS side of
+// such a load is fixed, the swizzle is applied on the global side: the lane that owns
+// LDS slot (row, position p) fetches the chunk that belongs there.  The instruction is
+// issued through inline assembly so that the waits can be counted by hand
+// (s_waitcnt vmcnt(n) with the younger stages still outstanding).
+// Nothing can be zero-filled on this path: rows beyond the matrix are redirected to a
+// valid row (they only feed outputs that are never stored), and k must be a multiple
+// of BK (the caller falls back to the register-staged kernel otherwise).
+__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));     // expcnt, lgkmcnt untouched
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
+    const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
+    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n) {
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int CA = BM * (BK / 8) / NT, CB = BN * (BK / 8) / NT;      // 16-byte pieces per thread and stage
+    constexpr int STAGE = (BM + BN) * BK;                                 // elements
+    __shared__ __attribute__((aligned(16))) bf16_t lds[NS * STAGE];
+
+    const int nblk = tiles_m * tiles_n;
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int pid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
+    const int width = GROUP_M * tiles_n;
+    const int first_m = (pid / width) * GROUP_M;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int tile_m = first_m + (pid % width) % gsz;
+    const int tile_n = (pid % width) / gsz;
+    const int i0 = tile_m * BM, j0 = tile_n * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+
+    // Per-thread source pointers (advanced by one k step after every issue) for the LDS
+    // slots this thread's lane position fills.
+    const bf16_t* ga[CA];
+    const bf16_t* gb[CB];
+    auto source = [&](const bf16_t* base, int ld, int row0, int nrows, int rows_in_tile, bool kc, int slot) {
+        if (kc) {
+            const int row = slot >> 3, p = slot & 7;
+            const int c = p ^ (row & 7) ^ ((row >> 3) & 7);
+            const int gr = min(row0 + row, nrows - 1);
+            return base + (size_t)gr * ld + c * 8;
+        }
+        const int per_row = rows_in_tile / 8;
+        const int kk = slot / per_row, pc = slot % per_row;
+        const int ic = ((((pc >> 1) ^ (kk & 3)) << 1) | (pc & 1));
+        int gi = row0 + ic * 8;
+        if (gi >= nrows) gi = 0;
+        return base + (size_t)kk * ld + gi;
+    };
+#pragma unroll
+    for (int it = 0; it < CA; ++it) ga[it] = source(A, lda, i0, m, BM, A_KC, it * NT + tid);
+#pragma unroll
+    for (int it = 0; it < CB; ++it) gb[it] = source(B, ldb, j0, n, BN, B_KC, it * NT + tid);
+    const size_t step_a = A_KC ? (size_t)BK : (size_t)BK * lda;
+    const size_t step_b = B_KC ? (size_t)BK : (size_t)BK * ldb;
+    // LDS byte address of stage 0 (32-bit pointer in the LDS address space)
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)lds;
+
+    auto issue = [&](int stage) {
+        const unsigned sa = lds0 + (unsigned)(stage * STAGE) * 2u + (unsigned)wave * 1024u;
+#pragma unroll
+        for (int it = 0; it < CA; ++it) { lds_dma16(ga[it], sa + it * NT * 16); ga[it] += step_a; }
+        const unsigned sb = sa + BM * BK * 2;
+#pragma unroll
+        for (int it = 0; it < CB; ++it) { lds_dma16(gb[it], sb + it * NT * 16); gb[it] += step_b; }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    const int KT = k / BK;
+#pragma unroll
+    for (int st = 0; st < NS - 1; ++st)
+        if (st < KT) issue(st);
+    int cur = 0, nxt = NS - 1;                 // stage computed now / stage the next issue fills
+    for (int kt = 0; kt < KT; ++kt) {
+        // the oldest outstanding group (step kt) must have landed; up to NS-2 younger ones may fly on
+        if (kt + NS - 2 < KT) wait_vmcnt<(NS - 2) * (CA + CB)>(); else wait_vmcnt<0>();
+        __syncthreads();                       // every wavefront's part of step kt is in LDS; step kt-1 is consumed
+        if (kt + NS - 1 < KT) issue(nxt);
+        const bf16_t* As = lds + cur * STAGE;
+        const bf16_t* Bs = As + BM * BK;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a) af[a] = read_frag<BM, A_KC>(As, wm0 + a * 32, kk, lane);
+#pragma unroll
+            for (int b = 0; b < TN; ++b) bfr[b] = read_frag<BN, B_KC>(Bs, wn0 + b * 32, kk, lane);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+        }
+        cur = cur + 1 == NS ? 0 : cur + 1;
+        nxt = nxt + 1 == NS ? 0 : nxt + 1;
+    }
+
+    const int rb0 = i0 + wm0, cb0 = j0 + wn0;
+#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
+    switch (epi) {
+        case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
+        case EPI_BIAS: CHIMERA_EPI(EPI_BIAS, false, false); break;
+        case EPI_BIAS_GELU: CHIMERA_EPI(EPI_BIAS_GELU, false, false); break;
+        case EPI_BIAS_RESIDUAL:
+            if (res_types == 0) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, false);
+            else if (res_types == 1) CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, false);
+            else if (res_types == 2) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, true);
+            else CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, true);
+            break;
+        case EPI_DGELU: CHIMERA_EPI(EPI_DGELU, false, false); break;
+        default: CHIMERA_EPI(EPI_ACCUM_F32, false, false); break;
+    }
+#undef CHIMERA_EPI
+}
+
 struct TileChoice { int bm, bn, splits; };
 
 TileChoice forced_tile() {
@@ -392,6 +508,23 @@ int launch_layout(const GemmArgs& g, int splits, hipStream_t s) {
     return CHIMERA_OK;
 }
 
+template <int BM, int BN, int WGM, int WGN, int NS>
+int launch_async(const GemmArgs& g, hipStream_t s) {
+    const int tm = (g.m + BM - 1) / BM, tn = (g.n + BN - 1) / BN;
+    const dim3 grid(tm * tn), block(WGM * WGN * 64);
+#define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                                \
+    hipLaunchKernelGGL((gemm_bf16_async_kernel<BM, BN, WGM, WGN, NS, AKC, BKC>), grid, block, 0, s,                   \
+                       (const bf16_t*)g.a, (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c,        \
+                       (bf16_t*)g.c2, g.m, g.n, g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf,                            \
+                       (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn)
+    if (g.a_kc && !g.b_kc) CHIMERA_GEMM_LAUNCH(true, false);
+    else if (g.a_kc && g.b_kc) CHIMERA_GEMM_LAUNCH(true, true);
+    else CHIMERA_GEMM_LAUNCH(false, false);
+#undef CHIMERA_GEMM_LAUNCH
+    CHIMERA_LAUNCH_CHECK("bf16 gemm (async)");
+    return CHIMERA_OK;
+}
+
 }  // namespace
 
 bool gemm_mfma_supports(const GemmArgs& g) {
@@ -424,6 +557,15 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     const TileChoice t = choose_tile(g);
     if (t.splits > 1 && (size_t)((g.m + 255) / 256) * ((g.n + 255) / 256) * sizeof(unsigned) > SPLITK_COUNTER_BYTES)
         return fail(CHIMERA_EINVAL, "too many tiles for split-K");
+    // the async kernels cannot zero-fill: whole k steps only, and at least 8 rows on each side
+    // Two stages measured as fast as three or four on MI355X, and leave room for two
+    // 128x128 workgroups per CU.
+    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");                 // tuning aid: 0 = register-staged kernels
+    const bool can_async = g.k % BK == 0 && g.m >= 8 && g.n >= 8 && t.splits == 1 && !(mode && mode[0] == '0');
+    if (can_async) {
+        if (t.bm == 256 && t.bn == 256) return launch_async<256, 256, 2, 4, 2>(g, s);
+        if (t.bm == 128 && t.bn == 128) return launch_async<128, 128, 2, 2, 2>(g, s);
+    }
     if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4, 1>(g, t.splits, s);
     if (t.bm == 128 && t.bn == 128) return launch_layout<128, 128, 2, 2, 1>(g, 1, s);
     return fail(CHIMERA_EINVAL, "no %dx%d gemm tile", t.bm, t.bn);
