@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="single stream per stage (analysis only)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs one Chimera worker on ONE GPU; --gpus %d is not supported "
@@ -70,7 +71,7 @@ def main():
     stages = []
     for pipe, stage_id in ((0, rank), (1, D - 1 - rank)):
         st = b.Stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, dtype, causal=cfg.causal,
-                     stash_slots=need[pipe])
+                     stash_slots=need[pipe], overlap=not args.no_overlap)
         st.set_weights(synth.flatten_params(synth.make_stage_params(cfg.hidden, cfg.layers, stage_id, 0, cfg.dtype)))
         stages.append(st)
     tdt = torch.float32 if dtype == b.F32 else torch.bfloat16

@@ -22,8 +22,10 @@
 // each 16-lane group the i-th 16-bit element of the data addressed by lanes
 // 4e + i/4 (e = 0..3), i.e. column i of a 4 x 16 block - four consecutive k of one
 // row.  Two such reads give the same 8 k values the other flavour gets from one
-// 16-byte load.  The 32-byte column blocks of row k are stored at block ^ (k & 3)
-// so that the four rows of a transposing read use all 32 banks.  No transposed
+// 16-byte load.  The 32-byte column blocks of row k are stored at block ^ 2(k & 3):
+// one bank cycle serves 32 lanes = two adjacent column blocks x four rows, and this
+// puts those eight 32-byte pieces on eight different bank groups (measured: without
+// it half of the LDS cycles of the wgrad kernel were bank conflicts).  No transposed
 // copy of any activation or weight exists in HBM, and no data is shuffled in
 // registers.
 //
@@ -53,7 +55,7 @@ typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 
 // LDS element offset of the 16-byte chunk `ic` (8 rows) of k-row `k` in a [BK][ROWS] tile
 template <int ROWS> __device__ __forceinline__ int mc_off(int k, int ic) {
-    return k * ROWS + (((ic >> 1) ^ (k & 3)) << 4) + ((ic & 1) << 3);
+    return k * ROWS + (((ic >> 1) ^ ((k & 3) << 1)) << 4) + ((ic & 1) << 3);
 }
 
 template <int ROWS, int NT, bool KC> struct Staged {
@@ -120,8 +122,8 @@ __device__ __forceinline__ bf16x8 read_frag(const bf16_t* lds, int r0, int kk, i
         const int i = lane & 15, blk = (r0 >> 4) + ((lane >> 4) & 1);      // 16-row column block of this lane group
         const int k = kk * 16 + (lane >> 5) * 8 + (i >> 2);                // row this lane addresses (first read)
         typedef bf16x4 __attribute__((address_space(3))) * lds_v4;
-        const bf16_t* p0 = lds + k * ROWS + ((blk ^ (k & 3)) << 4) + ((i & 3) << 2);
-        const bf16_t* p1 = lds + (k + 4) * ROWS + ((blk ^ ((k + 4) & 3)) << 4) + ((i & 3) << 2);
+        const bf16_t* p0 = lds + k * ROWS + ((blk ^ ((k & 3) << 1)) << 4) + ((i & 3) << 2);
+        const bf16_t* p1 = p0 + 4 * ROWS;                                  // rows k+4..k+7: same swizzle
         const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p0);
         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p1);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -379,7 +381,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
         }
         const int per_row = rows_in_tile / 8;
         const int kk = slot / per_row, pc = slot % per_row;
-        const int ic = ((((pc >> 1) ^ (kk & 3)) << 1) | (pc & 1));
+        const int ic = ((((pc >> 1) ^ ((kk & 3) << 1)) << 1) | (pc & 1));
         int gi = row0 + ic * 8;
         if (gi >= nrows) gi = 0;
         return base + (size_t)kk * ld + gi;
@@ -564,7 +566,10 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     const bool can_async = g.k % BK == 0 && g.m >= 8 && g.n >= 8 && t.splits == 1 && !(mode && mode[0] == '0');
     if (can_async) {
         if (t.bm == 256 && t.bn == 256) return launch_async<256, 256, 2, 4, 2>(g, s);
-        if (t.bm == 128 && t.bn == 128) return launch_async<128, 128, 2, 2, 2>(g, s);
+        if (t.bm == 128 && t.bn == 128) {
+            if (mode && mode[0] == '4') return launch_async<128, 128, 2, 2, 4>(g, s);
+            return launch_async<128, 128, 2, 2, 2>(g, s);
+        }
     }
     if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4, 1>(g, t.splits, s);
     if (t.bm == 128 && t.bn == 128) return launch_layout<128, 128, 2, 2, 1>(g, 1, s);
