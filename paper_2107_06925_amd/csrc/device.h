@@ -75,16 +75,23 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// tanh(x) = 1 - 2 / (1 + exp(2x)), on the hardware exp2 and reciprocal; absolute error below
+// 1e-6, exact limits for large |x| (exp overflows to inf -> 1, underflows to 0 -> -1).
+__device__ __forceinline__ float fast_tanh(float x) {
+    const float e = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);      // exp(2x)
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
 // GeLU, tanh form: 0.5 u (1 + tanh(sqrt(2/pi) (u + 0.044715 u^3))); erf form: u Phi(u).
 __device__ __forceinline__ float gelu_f(float u, int erf_form) {
     if (erf_form) return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f));
-    const float t = tanhf(0.79788456080286536f * (u + 0.044715f * u * u * u));
+    const float t = fast_tanh(0.79788456080286536f * (u + 0.044715f * u * u * u));
     return 0.5f * u * (1.0f + t);
 }
 __device__ __forceinline__ float gelu_grad_f(float u, int erf_form) {
     if (erf_form)
         return 0.5f * (1.0f + erff(u * 0.70710678118654752f)) + u * __expf(-0.5f * u * u) * 0.39894228040143268f;
-    const float t = tanhf(0.79788456080286536f * (u + 0.044715f * u * u * u));
+    const float t = fast_tanh(0.79788456080286536f * (u + 0.044715f * u * u * u));
     return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * 0.79788456080286536f * (1.0f + 3.0f * 0.044715f * u * u);
 }
 

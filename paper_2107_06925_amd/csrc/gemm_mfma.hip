@@ -131,43 +131,89 @@ __device__ __forceinline__ bf16x8 read_frag(const bf16_t* lds, int r0, int kk, i
 }
 
 // Epilogue of one wavefront.  Accumulator register r of lane l holds
-// C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
+// C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile: one column per lane, which
+// would mean 2-byte global accesses.  So each 32-row band of the wavefront's
+// tile goes through a wavefront-private LDS slab ([32][WN + 8] floats, the
+// padding keeps the two lane halves on different banks) and comes back as 8
+// consecutive columns per lane; bias, residual, GeLU operands and the results
+// then move in 16-byte pieces, 128 contiguous bytes per 8 lanes.
+template <int TN> struct EpiSlab {
+    static constexpr int WN = TN * 32, STRIDE = WN + 8, FLOATS = 32 * STRIDE;
+};
+
+__device__ __forceinline__ void load8(const bf16_t* p, float* o) { load_vec<bf16_t>(p, o); }
+__device__ __forceinline__ void load8(const float* p, float* o) { load_vec<float>(p, o); load_vec<float>(p + 4, o + 4); }
+__device__ __forceinline__ void store8(bf16_t* p, const float* v) { store_vec<bf16_t>(p, v); }
+__device__ __forceinline__ void store8(float* p, const float* v) { store_vec<float>(p, v); store_vec<float>(p + 4, v + 4); }
+
 template <int EPI, bool RF32, bool CF32, int TM, int TN>
-__device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], int row_base, int col_base, int m, int n,
-                                         const bf16_t* __restrict__ bias, const bf16_t* __restrict__ R,
+__device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* slab, int row_base, int col_base, int m,
+                                         int n, const bf16_t* __restrict__ bias, const bf16_t* __restrict__ R,
                                          void* __restrict__ c, bf16_t* __restrict__ C2, int erf_form, int lane) {
+    constexpr int WN = EpiSlab<TN>::WN, STRIDE = EpiSlab<TN>::STRIDE;
+    constexpr int CPR = WN / 8;                // 8-column pieces per row
+    constexpr int RPP = 64 / CPR;              // rows covered by the 64 lanes at once
     bf16_t* C = (bf16_t*)c;
     float* Cf = (float*)c;
+    const float* Rf = reinterpret_cast<const float*>(R);
     const int l32 = lane & 31, lhi = lane >> 5;
+    const int pr = lane / CPR, pc = (lane % CPR) * 8;
+    const int gcol = col_base + pc;
+    float bv[8];
 #pragma unroll
-    for (int b = 0; b < TN; ++b) {
-        const int col = col_base + b * 32 + l32;
-        if (col >= n) continue;
-        float bv = 0.f;
-        if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RESIDUAL) bv = (float)bias[col];
+    for (int e = 0; e < 8; ++e) bv[e] = 0.f;
+    if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RESIDUAL)
+        if (gcol < n) load8(bias + gcol, bv);
 #pragma unroll
-        for (int a = 0; a < TM; ++a) {
+    for (int a = 0; a < TM; ++a) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row_base + a * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-                if (row >= m) continue;
-                const size_t idx = (size_t)row * n + col;
-                const float v = acc[a][b][r];
-                if constexpr (EPI == EPI_NONE) C[idx] = (bf16_t)v;
-                else if constexpr (EPI == EPI_BIAS) C[idx] = (bf16_t)(v + bv);
-                else if constexpr (EPI == EPI_BIAS_GELU) {
-                    const float u = v + bv;
-                    C[idx] = (bf16_t)u;
-                    C2[idx] = (bf16_t)gelu_f(u, erf_form);
-                } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
-                    const float rv = RF32 ? reinterpret_cast<const float*>(R)[idx] : (float)R[idx];
-                    if constexpr (CF32) Cf[idx] = v + bv + rv;
-                    else C[idx] = (bf16_t)(v + bv + rv);
-                }
-                else if constexpr (EPI == EPI_DGELU) C[idx] = (bf16_t)(v * gelu_grad_f((float)R[idx], erf_form));
-                else Cf[idx] += v;
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) slab[(8 * (r >> 2) + 4 * lhi + (r & 3)) * STRIDE + b * 32 + l32] = acc[a][b][r];
+        __builtin_amdgcn_s_waitcnt(0xc07f);                   // lgkmcnt(0): the slab is written (wavefront-private)
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < 32 / RPP; ++j) {
+            const int lr = j * RPP + pr;
+            const int grow = row_base + a * 32 + lr;
+            float v[8];
+            load_vec<float>(slab + lr * STRIDE + pc, v);
+            load_vec<float>(slab + lr * STRIDE + pc + 4, v + 4);
+            if (grow >= m || gcol >= n) continue;
+            const size_t idx = (size_t)grow * n + gcol;
+            if constexpr (EPI == EPI_NONE) {
+                store8(C + idx, v);
+            } else if constexpr (EPI == EPI_BIAS) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += bv[e];
+                store8(C + idx, v);
+            } else if constexpr (EPI == EPI_BIAS_GELU) {
+                float g[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { v[e] += bv[e]; g[e] = gelu_f(v[e], erf_form); }
+                store8(C + idx, v);
+                store8(C2 + idx, g);
+            } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
+                float rv[8];
+                if constexpr (RF32) load8(Rf + idx, rv); else load8(R + idx, rv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += bv[e] + rv[e];
+                if constexpr (CF32) store8(Cf + idx, v); else store8(C + idx, v);
+            } else if constexpr (EPI == EPI_DGELU) {
+                float u[8];
+                load8(R + idx, u);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], erf_form);
+                store8(C + idx, v);
+            } else {
+                float old[8];
+                load8(Cf + idx, old);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += old[e];
+                store8(Cf + idx, v);
             }
         }
+        __builtin_amdgcn_wave_barrier();                      // all lanes have read the slab before it is rewritten
     }
 }
 
@@ -305,7 +351,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
     }
 
     const int rb0 = i0 + wm0, cb0 = j0 + wn0;
-#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
+    // the operand tiles in LDS are dead once every wavefront has left the k loop; each
+    // wavefront then stages its output through its own slab there
+    static_assert(sizeof(lds) >= (size_t)WGM * WGN * EpiSlab<TN>::FLOATS * sizeof(float), "LDS too small for the epilogue");
+    __syncthreads();
+    float* slab = reinterpret_cast<float*>(lds) + (size_t)(tid >> 6) * EpiSlab<TN>::FLOATS;
+#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, slab, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
     switch (epi) {
         case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
         case EPI_BIAS: CHIMERA_EPI(EPI_BIAS, false, false); break;
@@ -442,7 +493,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
     }
 
     const int rb0 = i0 + wm0, cb0 = j0 + wn0;
-#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
+    // the operand tiles in LDS are dead once every wavefront has left the k loop; each
+    // wavefront then stages its output through its own slab there
+    static_assert(sizeof(lds) >= (size_t)WGM * WGN * EpiSlab<TN>::FLOATS * sizeof(float), "LDS too small for the epilogue");
+    __syncthreads();
+    float* slab = reinterpret_cast<float*>(lds) + (size_t)(tid >> 6) * EpiSlab<TN>::FLOATS;
+#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, slab, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
     switch (epi) {
         case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
         case EPI_BIAS: CHIMERA_EPI(EPI_BIAS, false, false); break;
