@@ -11,7 +11,7 @@ namespace chimera {
 namespace {
 
 constexpr int LN_WAVES = 4;        // wavefronts (rows in flight) per block
-constexpr int LNB_ROWS = 16;       // rows per block in the LayerNorm backward
+constexpr int LNB_ROWS = 8;        // rows per block in the LayerNorm backward
 constexpr int CS_ROWS = 64;        // rows per block in the column sum
 
 // ------------------------------------------------------------- LayerNorm fwd
