@@ -221,6 +221,19 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind,
                     const void* d_bias, const void* d_r,
                     void* d_c, void* d_c2, void* d_workspace, size_t workspace_bytes,
                     void* hip_stream);
+/* `count` (1..4) products C_p[m_p, n_p] (float) += A_p^T-stored-[k, m_p] x B_p-stored-[k, n_p]
+ * in ONE launch: the weight gradients dW += X^T dY of one Transformer block (gradient
+ * accumulation over micro-batches, section 3.1 of the paper; the four linear layers of a
+ * block, section 4.1).  bf16 operands only, one contraction length k (a multiple of 64) for
+ * all products, m_p and n_p multiples of 8 and at least 8, 16-byte aligned pointers,
+ * leading dimensions lda_p >= m_p, ldb_p >= n_p (multiples of 8), C_p has leading dimension
+ * n_p.  The h_* arguments are host arrays of `count` entries (read before the call
+ * returns); the pointers in them are device pointers.  Results equal `count` calls of
+ * chimera_op_gemm with epilogue 5.  EINVAL for anything else (nothing is launched). */
+int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, int k,
+                                     const void* const* h_a, const int* h_lda,
+                                     const void* const* h_b, const int* h_ldb,
+                                     float* const* h_c, void* hip_stream);
 /* y = LN(x) gamma + beta; mean, rstd [rows] float are written for the backward. */
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x,
                              const void* d_gamma, const void* d_beta, void* d_y,

@@ -59,6 +59,7 @@ _SIGNATURES = {
     "chimera_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
+    "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_bwd_scratch_floats": (_sz, [_i, _i]),
     "chimera_op_layernorm_bwd": (_i, [_i, _i, _i] + [_p] * 11),
@@ -275,6 +276,19 @@ def chimera_op_gemm(a, b, c, m, n, k, a_kc, b_kc, epilogue=EPI_NONE, bias=None, 
     check(lib().chimera_op_gemm(_dt(a), impl, epilogue, int(gelu_erf), m, n, k, _ptr(a), lda, int(a_kc), _ptr(b), ldb,
                                 int(b_kc), _ptr(bias), _ptr(r), _ptr(c), _ptr(c2), _ptr(ws),
                                 ws.numel() if ws is not None else 0, _stream(a)))
+
+
+def chimera_op_gemm_group_accumulate(problems, k):
+    """problems: list of (a [k, m] bf16, b [k, n] bf16, c [m, n] float32) device tensors."""
+    cnt = len(problems)
+    ints = lambda v: (C.c_int * cnt)(*v)
+    ptrs = lambda v: (C.c_void_p * cnt)(*[t.data_ptr() for t in v])
+    a, b, c = zip(*problems) if cnt else ((), (), ())
+    m = [t.shape[1] for t in a]
+    n = [t.shape[1] for t in b]
+    check(lib().chimera_op_gemm_group_accumulate(cnt, ints(m), ints(n), k, ptrs(a), ints([t.stride(0) for t in a]), ptrs(b),
+                                                 ints([t.stride(0) for t in b]), ptrs(c),
+                                                 _stream(a[0]) if cnt else None))
 
 
 def chimera_op_layernorm_fwd(x, gamma, beta, y, mean, rstd):

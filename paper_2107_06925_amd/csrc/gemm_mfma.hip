@@ -47,6 +47,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;
 constexpr int GROUP_M = 8;       // tile rows per raster group
+constexpr int NUM_CUS = 256;     // compute units of an MI355X
 constexpr size_t SPLITK_COUNTER_BYTES = 4096;
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
@@ -243,7 +244,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
-    const int l32 = lane & 31, lhi = lane >> 5;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -393,12 +393,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));     // expcnt, lgkmcnt untouched
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
+// One output tile; `block_id` numbers the tiles of this product.  ONLY_EPI >= 0 compiles
+// that epilogue alone.
+template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_KC, int ONLY_EPI>
+__device__ __forceinline__ void gemm_async_tile(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n) {
-    constexpr int NT = WGM * WGN * 64;
+    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n, int block_id) {
+    constexpr int NT = WGM * WGN * WGK * 64;
+    constexpr int KSUB = BK / 16 / WGK;                                   // 16-wide k slices per wavefront and step
+    static_assert(KSUB >= 1 && KSUB * WGK * 16 == BK, "k split must divide the step");
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int CA = BM * (BK / 8) / NT, CB = BN * (BK / 8) / NT;      // 16-byte pieces per thread and stage
@@ -406,7 +410,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
     __shared__ __attribute__((aligned(16))) bf16_t lds[NS * STAGE];
 
     const int nblk = tiles_m * tiles_n;
-    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int xcd = block_id & 7, local = block_id >> 3;
     const int pid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
     const int width = GROUP_M * tiles_n;
     const int first_m = (pid / width) * GROUP_M;
@@ -417,7 +421,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    const int wk = wave / (WGM * WGN), wmn = wave % (WGM * WGN);       // k slice, position in the tile
+    const int wm0 = (wmn / WGN) * WM, wn0 = (wmn % WGN) * WN;
 
     // Per-thread source pointers (advanced by one k step after every issue) for the LDS
     // slots this thread's lane position fills.
@@ -476,7 +481,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
         const bf16_t* As = lds + cur * STAGE;
         const bf16_t* Bs = As + BM * BK;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
+        for (int ks = 0; ks < KSUB; ++ks) {
+            const int kk = wk * KSUB + ks;
             bf16x8 af[TM], bfr[TN];
 #pragma unroll
             for (int a = 0; a < TM; ++a) af[a] = read_frag<BM, A_KC>(As, wm0 + a * 32, kk, lane);
@@ -492,27 +498,105 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_async_kernel(
         nxt = nxt + 1 == NS ? 0 : nxt + 1;
     }
 
-    const int rb0 = i0 + wm0, cb0 = j0 + wn0;
+    const int cb0 = j0 + wn0;
     // the operand tiles in LDS are dead once every wavefront has left the k loop; each
     // wavefront then stages its output through its own slab there
-    static_assert(sizeof(lds) >= (size_t)WGM * WGN * EpiSlab<TN>::FLOATS * sizeof(float), "LDS too small for the epilogue");
+    static_assert(sizeof(lds) >= (size_t)(NT / 64) * EpiSlab<TN>::FLOATS * sizeof(float), "LDS too small for the epilogue");
     __syncthreads();
     float* slab = reinterpret_cast<float*>(lds) + (size_t)(tid >> 6) * EpiSlab<TN>::FLOATS;
-#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, slab, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
-    switch (epi) {
-        case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
-        case EPI_BIAS: CHIMERA_EPI(EPI_BIAS, false, false); break;
-        case EPI_BIAS_GELU: CHIMERA_EPI(EPI_BIAS_GELU, false, false); break;
-        case EPI_BIAS_RESIDUAL:
-            if (res_types == 0) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, false);
-            else if (res_types == 1) CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, false);
-            else if (res_types == 2) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, true);
-            else CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, true);
-            break;
-        case EPI_DGELU: CHIMERA_EPI(EPI_DGELU, false, false); break;
-        default: CHIMERA_EPI(EPI_ACCUM_F32, false, false); break;
-    }
+    auto finish = [&](const auto& out, int rb0) {
+#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF>(out, slab, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
+        if constexpr (ONLY_EPI == EPI_ACCUM_F32) { CHIMERA_EPI(EPI_ACCUM_F32, false, false); return; }
+        switch (epi) {
+            case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
+            case EPI_BIAS: CHIMERA_EPI(EPI_BIAS, false, false); break;
+            case EPI_BIAS_GELU: CHIMERA_EPI(EPI_BIAS_GELU, false, false); break;
+            case EPI_BIAS_RESIDUAL:
+                if (res_types == 0) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, false);
+                else if (res_types == 1) CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, false);
+                else if (res_types == 2) CHIMERA_EPI(EPI_BIAS_RESIDUAL, false, true);
+                else CHIMERA_EPI(EPI_BIAS_RESIDUAL, true, true);
+                break;
+            case EPI_DGELU: CHIMERA_EPI(EPI_DGELU, false, false); break;
+            default: CHIMERA_EPI(EPI_ACCUM_F32, false, false); break;
+        }
 #undef CHIMERA_EPI
+    };
+    if constexpr (WGK == 1) {
+        finish(acc, i0 + wm0);
+    } else {
+        // Two wavefronts hold partial sums of the same WM x WN block (one per k slice).  Each
+        // keeps the upper or lower half of the rows: it hands the other half to its partner
+        // through LDS, adds what the partner hands over (one float addition per element, so the
+        // result does not depend on which wavefront adds), and finishes its half.
+        static_assert(WGK == 2 && TM % 2 == 0, "row halves");
+        constexpr int TMO = TM / 2;
+        constexpr int PER_WAVE = TMO * TN * 4 * 64;                      // float4 per wavefront
+        static_assert(sizeof(lds) >= (size_t)(NT / 64) * PER_WAVE * sizeof(float4), "LDS too small for the exchange");
+        float4* xch = reinterpret_cast<float4*>(lds);
+        float4* send = xch + (size_t)wave * PER_WAVE + lane;
+        const float4* recv = xch + (size_t)(wave ^ (WGM * WGN)) * PER_WAVE + lane;
+        f32x16 own[TMO][TN];
+#pragma unroll
+        for (int a = 0; a < TMO; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const f32x16 give = wk ? acc[a][b] : acc[TMO + a][b];
+                own[a][b] = wk ? acc[TMO + a][b] : acc[a][b];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    send[((a * TN + b) * 4 + q) * 64] = make_float4(give[4 * q], give[4 * q + 1], give[4 * q + 2], give[4 * q + 3]);
+            }
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < TMO; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = recv[((a * TN + b) * 4 + q) * 64];
+                    own[a][b][4 * q] += v.x;
+                    own[a][b][4 * q + 1] += v.y;
+                    own[a][b][4 * q + 2] += v.z;
+                    own[a][b][4 * q + 3] += v.w;
+                }
+        __syncthreads();                       // the exchange area becomes the slabs
+        finish(own, i0 + wm0 + wk * TMO * 32);
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
+    const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
+    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n) {
+    gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, -1>(A, B, bias, R, C, C2, m, n, k, lda, ldb, epi, erf_form,
+                                                                res_types, tiles_m, tiles_n, (int)blockIdx.x);
+}
+
+// Several products C_p (float) += A_p B_p of one launch: same contraction length and operand
+// layout, each with its own shapes and pointers.  Workgroups [first[p], first[p+1]) work on
+// product p, so small products no longer leave most of the chip idle for a launch of their
+// own.  (The weight gradients of one Transformer block are such a group.)
+constexpr int GROUP_MAX = 4;
+struct GemmGroup {
+    const bf16_t* a[GROUP_MAX];
+    const bf16_t* b[GROUP_MAX];
+    float* c[GROUP_MAX];
+    int m[GROUP_MAX], n[GROUP_MAX], lda[GROUP_MAX], ldb[GROUP_MAX], tiles_m[GROUP_MAX], tiles_n[GROUP_MAX];
+    int first[GROUP_MAX + 1];
+    int count, k;
+};
+
+template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_group_kernel(GemmGroup grp) {
+    int p = 0;
+#pragma unroll
+    for (int i = 1; i < GROUP_MAX; ++i)
+        if (i < grp.count && (int)blockIdx.x >= grp.first[i]) p = i;
+    gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, EPI_ACCUM_F32>(
+        grp.a[p], grp.b[p], nullptr, nullptr, grp.c[p], nullptr, grp.m[p], grp.n[p], grp.k, grp.lda[p], grp.ldb[p],
+        EPI_ACCUM_F32, 0, 0, grp.tiles_m[p], grp.tiles_n[p], (int)blockIdx.x - grp.first[p]);
 }
 
 struct TileChoice { int bm, bn, splits; };
@@ -566,12 +650,12 @@ int launch_layout(const GemmArgs& g, int splits, hipStream_t s) {
     return CHIMERA_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS>
+template <int BM, int BN, int WGM, int WGN, int WGK, int NS>
 int launch_async(const GemmArgs& g, hipStream_t s) {
     const int tm = (g.m + BM - 1) / BM, tn = (g.n + BN - 1) / BN;
-    const dim3 grid(tm * tn), block(WGM * WGN * 64);
+    const dim3 grid(tm * tn), block(WGM * WGN * WGK * 64);
 #define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                                \
-    hipLaunchKernelGGL((gemm_bf16_async_kernel<BM, BN, WGM, WGN, NS, AKC, BKC>), grid, block, 0, s,                   \
+    hipLaunchKernelGGL((gemm_bf16_async_kernel<BM, BN, WGM, WGN, WGK, NS, AKC, BKC>), grid, block, 0, s,                   \
                        (const bf16_t*)g.a, (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c,        \
                        (bf16_t*)g.c2, g.m, g.n, g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf,                            \
                        (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn)
@@ -580,6 +664,14 @@ int launch_async(const GemmArgs& g, hipStream_t s) {
     else CHIMERA_GEMM_LAUNCH(false, false);
 #undef CHIMERA_GEMM_LAUNCH
     CHIMERA_LAUNCH_CHECK("bf16 gemm (async)");
+    return CHIMERA_OK;
+}
+
+template <int WGK, int NS>
+int launch_group(const GemmGroup& grp, hipStream_t s) {
+    const dim3 grid(grp.first[grp.count]), block(2 * 2 * WGK * 64);
+    hipLaunchKernelGGL((gemm_bf16_async_group_kernel<128, 128, 2, 2, WGK, NS, false, false>), grid, block, 0, s, grp);
+    CHIMERA_LAUNCH_CHECK("bf16 gemm group");
     return CHIMERA_OK;
 }
 
@@ -615,21 +707,58 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     const TileChoice t = choose_tile(g);
     if (t.splits > 1 && (size_t)((g.m + 255) / 256) * ((g.n + 255) / 256) * sizeof(unsigned) > SPLITK_COUNTER_BYTES)
         return fail(CHIMERA_EINVAL, "too many tiles for split-K");
-    // the async kernels cannot zero-fill: whole k steps only, and at least 8 rows on each side
-    // Two stages measured as fast as three or four on MI355X, and leave room for two
-    // 128x128 workgroups per CU.
+    // the async kernels cannot zero-fill: whole k steps only, and at least 8 rows on each side.
+    // 128x128 tiles: with fewer than two workgroups per CU, a workgroup of 4 wavefronts leaves
+    // one wavefront per SIMD, and nothing covers its LDS latency and the barrier of every k
+    // step; then 8 wavefronts share the tile, two per 64x64 block, each taking half of every
+    // k step (their partial sums meet in LDS at the end), over a 4-stage ring.  With two or
+    // more workgroups per CU the 2-stage ring (64 KiB of LDS, so two workgroups fit) is faster.
     const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");                 // tuning aid: 0 = register-staged kernels
     const bool can_async = g.k % BK == 0 && g.m >= 8 && g.n >= 8 && t.splits == 1 && !(mode && mode[0] == '0');
     if (can_async) {
-        if (t.bm == 256 && t.bn == 256) return launch_async<256, 256, 2, 4, 2>(g, s);
+        if (t.bm == 256 && t.bn == 256) return launch_async<256, 256, 2, 4, 1, 2>(g, s);
         if (t.bm == 128 && t.bn == 128) {
-            if (mode && mode[0] == '4') return launch_async<128, 128, 2, 2, 4>(g, s);
-            return launch_async<128, 128, 2, 2, 2>(g, s);
+            const long t128 = (long)((g.m + 127) / 128) * ((g.n + 127) / 128);
+            const bool ksplit = mode ? !std::strcmp(mode, "4k") : t128 < 2 * NUM_CUS;
+            if (ksplit) return launch_async<128, 128, 2, 2, 2, 3>(g, s);
+            return launch_async<128, 128, 2, 2, 1, 2>(g, s);
         }
     }
     if (t.bm == 256 && t.bn == 256) return launch_layout<256, 256, 2, 4, 1>(g, t.splits, s);
     if (t.bm == 128 && t.bn == 128) return launch_layout<128, 128, 2, 2, 1>(g, 1, s);
     return fail(CHIMERA_EINVAL, "no %dx%d gemm tile", t.bm, t.bn);
+}
+
+bool gemm_mfma_group_supports(int count, const GemmArgs* g) {
+    if (count < 1 || count > GROUP_MAX || !g) return false;
+    for (int i = 0; i < count; ++i) {
+        if (g[i].a_kc || g[i].b_kc || g[i].epilogue != EPI_ACCUM_F32 || !gemm_mfma_supports(g[i])) return false;
+        if (g[i].k != g[0].k || g[i].k % BK || g[i].m < 8 || g[i].n < 8) return false;
+        if ((uintptr_t)g[i].c & 15) return false;
+    }
+    return true;
+}
+
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, void* stream) {
+    if (!gemm_mfma_group_supports(count, g))
+        return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
+                    "one contraction length (a multiple of %d)", GROUP_MAX, BK);
+    GemmGroup grp{};
+    grp.count = count; grp.k = g[0].k;
+    int tiles = 0;
+    for (int i = 0; i < count; ++i) {
+        grp.a[i] = (const bf16_t*)g[i].a; grp.b[i] = (const bf16_t*)g[i].b; grp.c[i] = (float*)g[i].c;
+        grp.m[i] = g[i].m; grp.n[i] = g[i].n; grp.lda[i] = g[i].lda; grp.ldb[i] = g[i].ldb;
+        grp.tiles_m[i] = (g[i].m + 127) / 128; grp.tiles_n[i] = (g[i].n + 127) / 128;
+        grp.first[i] = tiles;
+        tiles += grp.tiles_m[i] * grp.tiles_n[i];
+    }
+    for (int i = count; i <= GROUP_MAX; ++i) grp.first[i] = tiles;
+    // same choice as for a single product: two workgroups per CU or the k-sliced 8-wavefront form
+    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");
+    const bool ksplit = mode ? !std::strcmp(mode, "4k") : tiles < 2 * NUM_CUS;
+    if (ksplit) return launch_group<2, 3>(grp, (hipStream_t)stream);
+    return launch_group<1, 2>(grp, (hipStream_t)stream);
 }
 
 }  // namespace chimera

@@ -58,6 +58,9 @@ struct GemmArgs {
 int gemm_reference(int dtype, const GemmArgs& g, void* stream);
 int gemm_mfma_bf16(const GemmArgs& g, void* stream);
 bool gemm_mfma_supports(const GemmArgs& g);
+// `count` float-accumulating products (index-contiguous operands, one contraction length) in one launch
+bool gemm_mfma_group_supports(int count, const GemmArgs* g);
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, void* stream);
 size_t gemm_mfma_workspace_bytes(int m, int n, int splits);
 size_t gemm_mfma_workspace_need(int m, int n, int k);   // bytes the tile heuristic wants for this shape (0 = none)
 

@@ -186,13 +186,26 @@ int linear_dgrad(chimera_stage* st, int m, int n, int k, const void* dy, const v
     return gemm(st, g, PC_GEMM_DGRAD, st->stream);
 }
 // dW[k,n] += X[m,k]^T dY[m,n]: contraction over the tokens.
-int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const void* dy, float* dw, hipStream_t stream) {
+GemmArgs wgrad_args(int m, int n, int k, const void* x, const void* dy, float* dw) {
     GemmArgs g{};
     g.m = k; g.n = n; g.k = m;
     g.a = x; g.lda = k; g.a_kc = 0;
     g.b = dy; g.ldb = n; g.b_kc = 0;
     g.c = dw; g.epilogue = EPI_ACCUM_F32;
-    return gemm(st, g, PC_GEMM_WGRAD, stream);
+    return g;
+}
+int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const void* dy, float* dw, hipStream_t stream) {
+    return gemm(st, wgrad_args(m, n, k, x, dy, dw), PC_GEMM_WGRAD, stream);
+}
+// the four weight gradients of one block as one launch (bf16 matrix-core path only)
+bool wgrad_group_ok(const chimera_stage* st, const GemmArgs (&g)[4]) {
+    return st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_group_supports(4, g);
+}
+int wgrad_group(chimera_stage* st, const GemmArgs (&g)[4], hipStream_t stream) {
+    double flop = 0;
+    for (const GemmArgs& a : g) flop += 2.0 * a.m * a.n * a.k;
+    ProfScope prof(PC_GEMM_WGRAD, flop, stream);
+    return gemm_mfma_bf16_group(4, g, stream);
 }
 
 int attn_args(chimera_stage* st, AttnArgs& a) {
@@ -314,22 +327,35 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         const void* h2 = st->ST(slot, l, st->s_h2);
         const void* u = st->ST(slot, l, st->s_u);
         const void* g = st->ST(slot, l, st->s_g);
+        // With the matrix-core kernels the block's four weight gradients go out as one launch,
+        // once the last of their operands (dqkv) exists; otherwise each follows its operands.
+        const GemmArgs wg[4] = {wgrad_args(M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2)),
+                                wgrad_args(M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1)),
+                                wgrad_args(M, H, H, ctx, dx1, st->G(l, st->o_w_o)),
+                                wgrad_args(M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv))};
+        const bool grouped = wgrad_group_ok(st, wg);
         // y = x1 + g W2 + b2
-        TRY(fork_to_side(st, 0));
-        TRY(st_colsum(st, H, dy, st->G(l, st->o_b_fc2), scratch2, gs));
-        TRY(linear_wgrad(st, M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2), gs));
+        if (!grouped) {
+            TRY(fork_to_side(st, 0));
+            TRY(st_colsum(st, H, dy, st->G(l, st->o_b_fc2), scratch2, gs));
+            TRY(linear_wgrad(st, M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2), gs));
+        }
         TRY(linear_dgrad(st, M, H, 4 * H, dy, st->W(l, st->o_w_fc2), u, du, EPI_DGELU));       // du = dg * GeLU'(u)
         // u = h2 W1 + b1
-        TRY(fork_to_side(st, 1));
-        TRY(st_colsum(st, 4 * H, du, st->G(l, st->o_b_fc1), scratch2, gs));
-        TRY(linear_wgrad(st, M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1), gs));
+        if (!grouped) {
+            TRY(fork_to_side(st, 1));
+            TRY(st_colsum(st, 4 * H, du, st->G(l, st->o_b_fc1), scratch2, gs));
+            TRY(linear_wgrad(st, M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1), gs));
+        }
         TRY(linear_dgrad(st, M, 4 * H, H, du, st->W(l, st->o_w_fc1), nullptr, dh, EPI_NONE));
         TRY(st_ln_bwd(st, dh, x1, wide, (const float*)st->ST(slot, l, st->s_mean2), (const float*)st->ST(slot, l, st->s_rstd2),
                       st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch));
         // x1 = x + ctx Wo + bo
-        TRY(fork_to_side(st, 2));
-        TRY(st_colsum(st, H, dx1, st->G(l, st->o_b_o), scratch2, gs));
-        TRY(linear_wgrad(st, M, H, H, ctx, dx1, st->G(l, st->o_w_o), gs));
+        if (!grouped) {
+            TRY(fork_to_side(st, 2));
+            TRY(st_colsum(st, H, dx1, st->G(l, st->o_b_o), scratch2, gs));
+            TRY(linear_wgrad(st, M, H, H, ctx, dx1, st->G(l, st->o_w_o), gs));
+        }
         TRY(linear_dgrad(st, M, H, H, dx1, st->W(l, st->o_w_o), nullptr, dctx, EPI_NONE));
         AttnArgs a{};
         attn_args(st, a);
@@ -338,8 +364,16 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         TRY(st_attn_bwd(st, a));
         // qkv = h1 Wqkv + bqkv
         TRY(fork_to_side(st, 3));
-        TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch2, gs));
-        TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv), gs));
+        if (grouped) {
+            TRY(wgrad_group(st, wg, gs));
+            TRY(st_colsum(st, H, dy, st->G(l, st->o_b_fc2), scratch2, gs));
+            TRY(st_colsum(st, 4 * H, du, st->G(l, st->o_b_fc1), scratch2, gs));
+            TRY(st_colsum(st, H, dx1, st->G(l, st->o_b_o), scratch2, gs));
+            TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch2, gs));
+        } else {
+            TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch2, gs));
+            TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv), gs));
+        }
         if (st->have_side) HIP_TRY(hipEventRecord(st->ev_side[par], st->side));
         TRY(linear_dgrad(st, M, 3 * H, H, dqkv, st->W(l, st->o_w_qkv), nullptr, dh, EPI_NONE));
         // dx goes into the buffer that the block above read its dy from, also on the side stream
@@ -637,6 +671,24 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int
 }
 
 size_t chimera_op_gemm_workspace_bytes(int m, int n, int k) { return gemm_mfma_workspace_need(m, n, k); }
+
+int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, int k, const void* const* h_a,
+                                     const int* h_lda, const void* const* h_b, const int* h_ldb, float* const* h_c,
+                                     void* hip_stream) {
+    if (count < 1 || count > 4) return fail(CHIMERA_EINVAL, "group of %d products (1..4)", count);
+    if (!h_m || !h_n || !h_a || !h_lda || !h_b || !h_ldb || !h_c) return fail(CHIMERA_EINVAL, "NULL argument array");
+    GemmArgs g[4] = {};
+    for (int i = 0; i < count; ++i) {
+        if (!h_a[i] || !h_b[i] || !h_c[i]) return fail(CHIMERA_EINVAL, "NULL operand in product %d", i);
+        if (h_m[i] < 8 || h_n[i] < 8 || k < 1) return fail(CHIMERA_EINVAL, "product %d: sizes too small", i);
+        if (h_lda[i] < h_m[i] || h_ldb[i] < h_n[i]) return fail(CHIMERA_EINVAL, "product %d: leading dimension too small", i);
+        g[i].m = h_m[i]; g[i].n = h_n[i]; g[i].k = k;
+        g[i].a = h_a[i]; g[i].lda = h_lda[i]; g[i].a_kc = 0;
+        g[i].b = h_b[i]; g[i].ldb = h_ldb[i]; g[i].b_kc = 0;
+        g[i].c = h_c[i]; g[i].epilogue = EPI_ACCUM_F32;
+    }
+    return gemm_mfma_bf16_group(count, g, hip_stream);
+}
 
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x, const void* d_gamma, const void* d_beta,
                              void* d_y, float* d_mean, float* d_rstd, void* hip_stream) {

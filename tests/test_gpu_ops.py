@@ -104,6 +104,67 @@ def test_gemm_split_k_matches_unsplit_and_is_reproducible():
     del os.environ["CHIMERA_GEMM_TILE"]
 
 
+GROUPS = [
+    # (k, [(m, n), ...]): one block's weight gradients in miniature; ragged tiles; a single product
+    (256, [(128, 512), (512, 128), (128, 128), (128, 384)]),
+    (192, [(200, 136), (8, 8), (264, 520)]),
+    (64, [(136, 72)]),
+    (1024, [(256, 1024), (1024, 256), (256, 256), (256, 768)]),     # 48 tiles: the k-sliced 8-wavefront variant
+    (128, [(1024, 4096), (4096, 1024), (1024, 1024), (1024, 3072)]),   # 768 tiles: the two-workgroups-per-CU variant
+]
+
+
+@pytest.mark.parametrize("k,shapes", GROUPS)
+def test_gemm_group_accumulate(k, shapes):
+    """One launch for several dW += X^T dY equals the per-product oracle, twice in a row."""
+    import torch
+    print("gemm group", k, shapes, flush=True)
+    probs, want, c0s = [], [], []
+    for i, (m, n) in enumerate(shapes):
+        X = _rand((k, m), 10 + i, b.BF16)
+        dY = _rand((k, n), 20 + i, b.BF16)
+        c0 = np.random.default_rng(30 + i).standard_normal((m, n)).astype(np.float32)
+        probs.append((to_dev(X, b.BF16), to_dev(dY, b.BF16), torch.from_numpy(c0.copy()).cuda()))
+        want.append(X.astype(np.float64).T @ dY.astype(np.float64))
+        c0s.append(c0)
+    b.chimera_op_gemm_group_accumulate(probs, k)
+    b.chimera_op_gemm_group_accumulate(probs, k)
+    torch.cuda.synchronize()
+    for i, (_, _, c) in enumerate(probs):
+        assert_close(to_np(c) - c0s[i], 2 * want[i], b.BF16, "product %d" % i)
+
+
+def test_gemm_group_matches_single_launches_bitwise():
+    import torch
+    k, shapes = 320, [(136, 264), (264, 136), (128, 128)]
+    probs, singles = [], []
+    for i, (m, n) in enumerate(shapes):
+        X = to_dev(_rand((k, m), 40 + i, b.BF16), b.BF16)
+        dY = to_dev(_rand((k, n), 50 + i, b.BF16), b.BF16)
+        probs.append((X, dY, torch.zeros((m, n), device="cuda")))
+        singles.append(torch.zeros((m, n), device="cuda"))
+        b.chimera_op_gemm(X, dY, singles[-1], m, n, k, 0, 0, b.EPI_ACCUM_F32)
+    b.chimera_op_gemm_group_accumulate(probs, k)
+    torch.cuda.synchronize()
+    for (_, _, c), s1 in zip(probs, singles):
+        assert torch.equal(c, s1)
+
+
+def test_gemm_group_argument_errors():
+    import torch
+    X = torch.zeros((64, 16), device="cuda", dtype=torch.bfloat16)
+    c = torch.zeros((16, 16), device="cuda")
+    with pytest.raises(b.ChimeraError):
+        b.chimera_op_gemm_group_accumulate([(X, X, c)] * 5, 64)            # more than four products
+    with pytest.raises(b.ChimeraError):
+        b.chimera_op_gemm_group_accumulate([(X[:40], X[:40], c)], 40)      # k not a multiple of 64
+    Y = torch.zeros((64, 4), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(b.ChimeraError):
+        b.chimera_op_gemm_group_accumulate([(X, Y, torch.zeros((16, 4), device="cuda"))], 64)   # n < 8
+    with pytest.raises(b.ChimeraError):
+        b.chimera_op_gemm_group_accumulate([], 64)
+
+
 def test_gemm_argument_errors():
     import torch
     a = torch.zeros((16, 16), device="cuda")
