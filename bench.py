@@ -19,11 +19,11 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix throughput
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the weight-gradient GEMM kernel, from two rocprofv3 --pmc runs of this
-# script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the kernel's launches),
-# each scaled by what the same counter reads for a streaming kernel of known size
-# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (51280.0 * 2.00 + 12288.0) KiB.
-WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((51280.0 * 2.00 + 12288.0) * 1024)}
+# HBM bytes per launch of the grouped weight-gradient kernel, from two rocprofv3 --pmc runs of
+# this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the kernel's
+# launches), each scaled by what the same counter reads for a streaming kernel of known size
+# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (209221.5 * 2.00 + 49188.1) KiB.
+WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((209221.5 * 2.00 + 49188.1) * 1024)}
 
 
 def _cpu_baseline(cfg, blocks=6):
@@ -130,7 +130,8 @@ def main():
         wg = prof["gemm_wgrad"]
         achieved = wg["work"] / (wg["ms"] * 1e-3) / 1e12 if wg["ms"] else 0.0
         out["roofline"] = {
-            "kernel": ("gemm_bf16_async_kernel<128,128,2,2,2,0,0> (weight-gradient GEMMs, fp32 accumulate into dW)"
+            "kernel": ("gemm_bf16_async_group_kernel<128,128,2,2,1,2,0,0> (the four weight gradients of a block, "
+                       "dW += X^T dY in fp32, and their bias gradients, one launch per block and micro-batch)"
                        if dtype == b.BF16 else "gemm_ref_kernel (weight-gradient GEMMs)"),
             "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
@@ -168,6 +169,15 @@ def main():
                           "bubble_frac": st["bubbles"][rank] / st["makespan"], "stash_peak": max(st["stash_peak"])}
         out["pipeline_projection"] = proj
 
+    if dtype == b.BF16:
+        # what this chip sustains: register-resident MFMA loop on every SIMD, and a streaming copy
+        sink = torch.zeros(1, device="cuda")
+        src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        out["measured_ceiling"] = {"mfma_bf16_TFLOP/s": b.chimera_probe_mfma_bf16(sink),
+                                   "stream_copy_GB/s": b.chimera_probe_copy(src, dst),
+                                   "note": "register-resident 32x32x16 bf16 MFMA loop on all SIMDs; 256 MiB copy, read+write"}
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(cfg)
     print(json.dumps(out))

@@ -227,13 +227,15 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind,
  * block, section 4.1).  bf16 operands only, one contraction length k (a multiple of 64) for
  * all products, m_p and n_p multiples of 8 and at least 8, 16-byte aligned pointers,
  * leading dimensions lda_p >= m_p, ldb_p >= n_p (multiples of 8), C_p has leading dimension
- * n_p.  The h_* arguments are host arrays of `count` entries (read before the call
- * returns); the pointers in them are device pointers.  Results equal `count` calls of
+ * n_p.  h_bsum (may be NULL, and so may any entry): bsum_p[j] (float, n_p entries) +=
+ * sum over k of B_p(k, j), the bias gradient that belongs to dW_p; it costs no extra pass
+ * over B.  The h_* arguments are host arrays of `count` entries (read before the call
+ * returns); the pointers in them are device pointers.  The C_p equal `count` calls of
  * chimera_op_gemm with epilogue 5.  EINVAL for anything else (nothing is launched). */
 int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, int k,
                                      const void* const* h_a, const int* h_lda,
                                      const void* const* h_b, const int* h_ldb,
-                                     float* const* h_c, void* hip_stream);
+                                     float* const* h_c, float* const* h_bsum, void* hip_stream);
 /* y = LN(x) gamma + beta; mean, rstd [rows] float are written for the backward. */
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x,
                              const void* d_gamma, const void* d_beta, void* d_y,
@@ -261,6 +263,17 @@ int chimera_op_attention_bwd(int dtype, int impl, int batch, int seq, int heads,
                              int causal, const void* d_qkv, const void* d_ctx,
                              const float* d_lse, const void* d_dctx, void* d_dqkv,
                              float* d_delta, void* hip_stream);
+
+/* ------------------------------------------------------------ measured ceilings
+ * What the device sustains, to set beside the published peaks when the stage kernels'
+ * rates are reported (measurement only; the hot path never calls them).
+ * chimera_probe_mfma_bf16: every SIMD of the chip runs `iters` x 16 bf16 32x32x16 MFMAs on
+ * register-resident operands; *h_tflops receives the rate.  d_sink: 4 bytes of device
+ * memory (never written).  chimera_probe_copy: dst = src over `bytes` bytes (a multiple of
+ * 16, both pointers 16-byte aligned, buffers owned by the caller); *h_gbs receives
+ * (bytes read + bytes written) per second.  Both wait for their own launches. */
+int chimera_probe_mfma_bf16(float* d_sink, int iters, double* h_tflops, void* hip_stream);
+int chimera_probe_copy(const void* d_src, void* d_dst, size_t bytes, double* h_gbs, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -59,7 +59,7 @@ _SIGNATURES = {
     "chimera_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
-    "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p]),
+    "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_bwd_scratch_floats": (_sz, [_i, _i]),
     "chimera_op_layernorm_bwd": (_i, [_i, _i, _i] + [_p] * 11),
@@ -67,6 +67,8 @@ _SIGNATURES = {
     "chimera_op_colsum": (_i, [_i, _i, _i, _p, _p, _p, _p]),
     "chimera_op_attention_fwd": (_i, [_i] * 7 + [_p, _p, _p, _p]),
     "chimera_op_attention_bwd": (_i, [_i] * 7 + [_p] * 7),
+    "chimera_probe_mfma_bf16": (_i, [_p, _i, C.POINTER(C.c_double), _p]),
+    "chimera_probe_copy": (_i, [_p, _p, _sz, C.POINTER(C.c_double), _p]),
 }
 
 _lib = None
@@ -278,8 +280,9 @@ def chimera_op_gemm(a, b, c, m, n, k, a_kc, b_kc, epilogue=EPI_NONE, bias=None, 
                                 ws.numel() if ws is not None else 0, _stream(a)))
 
 
-def chimera_op_gemm_group_accumulate(problems, k):
-    """problems: list of (a [k, m] bf16, b [k, n] bf16, c [m, n] float32) device tensors."""
+def chimera_op_gemm_group_accumulate(problems, k, bsums=None):
+    """problems: list of (a [k, m] bf16, b [k, n] bf16, c [m, n] float32) device tensors;
+    bsums: optional list of float32 [n] tensors (or None) receiving += column sums of b."""
     cnt = len(problems)
     ints = lambda v: (C.c_int * cnt)(*v)
     ptrs = lambda v: (C.c_void_p * cnt)(*[t.data_ptr() for t in v])
@@ -288,6 +291,8 @@ def chimera_op_gemm_group_accumulate(problems, k):
     n = [t.shape[1] for t in b]
     check(lib().chimera_op_gemm_group_accumulate(cnt, ints(m), ints(n), k, ptrs(a), ints([t.stride(0) for t in a]), ptrs(b),
                                                  ints([t.stride(0) for t in b]), ptrs(c),
+                                                 None if bsums is None else (C.c_void_p * cnt)(
+                                                     *[None if t is None else t.data_ptr() for t in bsums]),
                                                  _stream(a[0]) if cnt else None))
 
 
@@ -320,3 +325,15 @@ def chimera_op_attention_fwd(qkv, ctx, lse, batch, seq, heads, head_dim, causal,
 def chimera_op_attention_bwd(qkv, ctx, lse, dctx, dqkv, delta, batch, seq, heads, head_dim, causal, impl=0):
     check(lib().chimera_op_attention_bwd(_dt(qkv), impl, batch, seq, heads, head_dim, int(causal), _ptr(qkv), _ptr(ctx),
                                          _ptr(lse), _ptr(dctx), _ptr(dqkv), _ptr(delta), _stream(qkv)))
+
+
+def chimera_probe_mfma_bf16(sink, iters=2000):
+    out = C.c_double(0)
+    check(lib().chimera_probe_mfma_bf16(_ptr(sink), iters, C.byref(out), _stream(sink)))
+    return out.value
+
+
+def chimera_probe_copy(src, dst):
+    out = C.c_double(0)
+    check(lib().chimera_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), C.byref(out), _stream(src)))
+    return out.value

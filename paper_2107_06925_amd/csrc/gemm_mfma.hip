@@ -399,7 +399,8 @@ template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_K
 __device__ __forceinline__ void gemm_async_tile(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n, int block_id) {
+    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n, int block_id,
+    float* __restrict__ bsum = nullptr) {
     constexpr int NT = WGM * WGN * WGK * 64;
     constexpr int KSUB = BK / 16 / WGK;                                   // 16-wide k slices per wavefront and step
     static_assert(KSUB >= 1 && KSUB * WGK * 16 == BK, "k split must divide the step");
@@ -468,6 +469,19 @@ __device__ __forceinline__ void gemm_async_tile(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+    // Optional by-product: bsum[j] += sum over the contraction index of B(k, j), i.e. an extra
+    // all-ones row of A.  The wavefronts at the top edge of the first tile row compute it
+    // with one more MFMA per 32 columns (every row of that accumulator is the column sum).
+    const bool col_sums = bsum != nullptr && tile_m == 0 && wm0 == 0;
+    f32x16 cs[TN];
+    bf16x8 ones;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) ones[q] = (bf16_t)1.0f;
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cs[b][r] = 0.f;
+
     const int KT = k / BK;
 #pragma unroll
     for (int st = 0; st < NS - 1; ++st)
@@ -493,6 +507,10 @@ __device__ __forceinline__ void gemm_async_tile(
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+            if constexpr (ONLY_EPI == EPI_ACCUM_F32)
+                if (col_sums)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) cs[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, bfr[b], cs[b], 0, 0, 0);
         }
         cur = cur + 1 == NS ? 0 : cur + 1;
         nxt = nxt + 1 == NS ? 0 : nxt + 1;
@@ -522,7 +540,23 @@ __device__ __forceinline__ void gemm_async_tile(
         }
 #undef CHIMERA_EPI
     };
+    // row 0 of a column-sum accumulator: register 0 of lanes 0..31
+    auto put_col_sums = [&](const float (&v)[TN]) {
+        if (lane < 32)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const int col = cb0 + b * 32 + lane;
+                if (col < n) bsum[col] += v[b];
+            }
+    };
     if constexpr (WGK == 1) {
+        if constexpr (ONLY_EPI == EPI_ACCUM_F32)
+            if (col_sums) {
+                float v[TN];
+#pragma unroll
+                for (int b = 0; b < TN; ++b) v[b] = cs[b][0];
+                put_col_sums(v);
+            }
         finish(acc, i0 + wm0);
     } else {
         // Two wavefronts hold partial sums of the same WM x WN block (one per k slice).  Each
@@ -534,6 +568,13 @@ __device__ __forceinline__ void gemm_async_tile(
         constexpr int PER_WAVE = TMO * TN * 4 * 64;                      // float4 per wavefront
         static_assert(sizeof(lds) >= (size_t)(NT / 64) * PER_WAVE * sizeof(float4), "LDS too small for the exchange");
         float4* xch = reinterpret_cast<float4*>(lds);
+        // column sums of the two k slices meet behind the exchange area
+        float* xcs = reinterpret_cast<float*>(xch + (size_t)(NT / 64) * PER_WAVE) + wn0;
+        static_assert(sizeof(lds) >= (size_t)(NT / 64) * PER_WAVE * sizeof(float4) + BN * sizeof(float), "LDS too small");
+        if constexpr (ONLY_EPI == EPI_ACCUM_F32)
+            if (col_sums && wk == 1 && lane < 32)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) xcs[b * 32 + lane] = cs[b][0];
         float4* send = xch + (size_t)wave * PER_WAVE + lane;
         const float4* recv = xch + (size_t)(wave ^ (WGM * WGN)) * PER_WAVE + lane;
         f32x16 own[TMO][TN];
@@ -560,6 +601,13 @@ __device__ __forceinline__ void gemm_async_tile(
                     own[a][b][4 * q + 2] += v.z;
                     own[a][b][4 * q + 3] += v.w;
                 }
+        if constexpr (ONLY_EPI == EPI_ACCUM_F32)
+            if (col_sums && wk == 0) {
+                float v[TN];
+#pragma unroll
+                for (int b = 0; b < TN; ++b) v[b] = cs[b][0] + (lane < 32 ? xcs[b * 32 + lane] : 0.f);
+                put_col_sums(v);
+            }
         __syncthreads();                       // the exchange area becomes the slabs
         finish(own, i0 + wm0 + wk * TMO * 32);
     }
@@ -583,6 +631,7 @@ struct GemmGroup {
     const bf16_t* a[GROUP_MAX];
     const bf16_t* b[GROUP_MAX];
     float* c[GROUP_MAX];
+    float* bsum[GROUP_MAX];      // optional: bsum[j] += sum_k B(k, j)
     int m[GROUP_MAX], n[GROUP_MAX], lda[GROUP_MAX], ldb[GROUP_MAX], tiles_m[GROUP_MAX], tiles_n[GROUP_MAX];
     int first[GROUP_MAX + 1];
     int count, k;
@@ -596,7 +645,7 @@ __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_group_ker
         if (i < grp.count && (int)blockIdx.x >= grp.first[i]) p = i;
     gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, EPI_ACCUM_F32>(
         grp.a[p], grp.b[p], nullptr, nullptr, grp.c[p], nullptr, grp.m[p], grp.n[p], grp.k, grp.lda[p], grp.ldb[p],
-        EPI_ACCUM_F32, 0, 0, grp.tiles_m[p], grp.tiles_n[p], (int)blockIdx.x - grp.first[p]);
+        EPI_ACCUM_F32, 0, 0, grp.tiles_m[p], grp.tiles_n[p], (int)blockIdx.x - grp.first[p], grp.bsum[p]);
 }
 
 struct TileChoice { int bm, bn, splits; };
@@ -739,7 +788,7 @@ bool gemm_mfma_group_supports(int count, const GemmArgs* g) {
     return true;
 }
 
-int gemm_mfma_bf16_group(int count, const GemmArgs* g, void* stream) {
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, void* stream) {
     if (!gemm_mfma_group_supports(count, g))
         return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
                     "one contraction length (a multiple of %d)", GROUP_MAX, BK);
@@ -748,6 +797,7 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, void* stream) {
     int tiles = 0;
     for (int i = 0; i < count; ++i) {
         grp.a[i] = (const bf16_t*)g[i].a; grp.b[i] = (const bf16_t*)g[i].b; grp.c[i] = (float*)g[i].c;
+        grp.bsum[i] = bsum ? bsum[i] : nullptr;
         grp.m[i] = g[i].m; grp.n[i] = g[i].n; grp.lda[i] = g[i].lda; grp.ldb[i] = g[i].ldb;
         grp.tiles_m[i] = (g[i].m + 127) / 128; grp.tiles_n[i] = (g[i].n + 127) / 128;
         grp.first[i] = tiles;

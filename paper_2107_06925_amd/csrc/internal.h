@@ -58,9 +58,10 @@ struct GemmArgs {
 int gemm_reference(int dtype, const GemmArgs& g, void* stream);
 int gemm_mfma_bf16(const GemmArgs& g, void* stream);
 bool gemm_mfma_supports(const GemmArgs& g);
-// `count` float-accumulating products (index-contiguous operands, one contraction length) in one launch
+// `count` float-accumulating products (index-contiguous operands, one contraction length) in one launch;
+// bsum (may be null, entries may be null): bsum[p][j] += sum_k B_p(k, j), the bias gradient of a linear layer
 bool gemm_mfma_group_supports(int count, const GemmArgs* g);
-int gemm_mfma_bf16_group(int count, const GemmArgs* g, void* stream);
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, void* stream);
 size_t gemm_mfma_workspace_bytes(int m, int n, int splits);
 size_t gemm_mfma_workspace_need(int m, int n, int k);   // bytes the tile heuristic wants for this shape (0 = none)
 

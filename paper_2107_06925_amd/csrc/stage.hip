@@ -201,11 +201,11 @@ int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const vo
 bool wgrad_group_ok(const chimera_stage* st, const GemmArgs (&g)[4]) {
     return st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_group_supports(4, g);
 }
-int wgrad_group(chimera_stage* st, const GemmArgs (&g)[4], hipStream_t stream) {
+int wgrad_group(chimera_stage* st, const GemmArgs (&g)[4], float* const (&db)[4], hipStream_t stream) {
     double flop = 0;
     for (const GemmArgs& a : g) flop += 2.0 * a.m * a.n * a.k;
     ProfScope prof(PC_GEMM_WGRAD, flop, stream);
-    return gemm_mfma_bf16_group(4, g, stream);
+    return gemm_mfma_bf16_group(4, g, db, stream);
 }
 
 int attn_args(chimera_stage* st, AttnArgs& a) {
@@ -365,11 +365,9 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         // qkv = h1 Wqkv + bqkv
         TRY(fork_to_side(st, 3));
         if (grouped) {
-            TRY(wgrad_group(st, wg, gs));
-            TRY(st_colsum(st, H, dy, st->G(l, st->o_b_fc2), scratch2, gs));
-            TRY(st_colsum(st, 4 * H, du, st->G(l, st->o_b_fc1), scratch2, gs));
-            TRY(st_colsum(st, H, dx1, st->G(l, st->o_b_o), scratch2, gs));
-            TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch2, gs));
+            // the bias gradients (column sums of dy, du, dx1, dqkv) come out of the same launch
+            float* const db[4] = {st->G(l, st->o_b_fc2), st->G(l, st->o_b_fc1), st->G(l, st->o_b_o), st->G(l, st->o_b_qkv)};
+            TRY(wgrad_group(st, wg, db, gs));
         } else {
             TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch2, gs));
             TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv), gs));
@@ -674,7 +672,7 @@ size_t chimera_op_gemm_workspace_bytes(int m, int n, int k) { return gemm_mfma_w
 
 int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, int k, const void* const* h_a,
                                      const int* h_lda, const void* const* h_b, const int* h_ldb, float* const* h_c,
-                                     void* hip_stream) {
+                                     float* const* h_bsum, void* hip_stream) {
     if (count < 1 || count > 4) return fail(CHIMERA_EINVAL, "group of %d products (1..4)", count);
     if (!h_m || !h_n || !h_a || !h_lda || !h_b || !h_ldb || !h_c) return fail(CHIMERA_EINVAL, "NULL argument array");
     GemmArgs g[4] = {};
@@ -687,7 +685,7 @@ int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, 
         g[i].b = h_b[i]; g[i].ldb = h_ldb[i]; g[i].b_kc = 0;
         g[i].c = h_c[i]; g[i].epilogue = EPI_ACCUM_F32;
     }
-    return gemm_mfma_bf16_group(count, g, hip_stream);
+    return gemm_mfma_bf16_group(count, g, h_bsum, hip_stream);
 }
 
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x, const void* d_gamma, const void* d_beta,

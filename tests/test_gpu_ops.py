@@ -114,12 +114,13 @@ GROUPS = [
 ]
 
 
+@pytest.mark.parametrize("with_bsum", [False, True])
 @pytest.mark.parametrize("k,shapes", GROUPS)
-def test_gemm_group_accumulate(k, shapes):
+def test_gemm_group_accumulate(k, shapes, with_bsum):
     """One launch for several dW += X^T dY equals the per-product oracle, twice in a row."""
     import torch
     print("gemm group", k, shapes, flush=True)
-    probs, want, c0s = [], [], []
+    probs, want, c0s, bs, bs0, want_b = [], [], [], [], [], []
     for i, (m, n) in enumerate(shapes):
         X = _rand((k, m), 10 + i, b.BF16)
         dY = _rand((k, n), 20 + i, b.BF16)
@@ -127,11 +128,18 @@ def test_gemm_group_accumulate(k, shapes):
         probs.append((to_dev(X, b.BF16), to_dev(dY, b.BF16), torch.from_numpy(c0.copy()).cuda()))
         want.append(X.astype(np.float64).T @ dY.astype(np.float64))
         c0s.append(c0)
-    b.chimera_op_gemm_group_accumulate(probs, k)
-    b.chimera_op_gemm_group_accumulate(probs, k)
+        # bias gradient of the same layer (column sums of dY); the odd products go without
+        b0 = np.random.default_rng(60 + i).standard_normal(n).astype(np.float32)
+        bs0.append(b0)
+        bs.append(torch.from_numpy(b0.copy()).cuda() if with_bsum and i % 2 == 0 else None)
+        want_b.append(dY.astype(np.float64).sum(axis=0))
+    b.chimera_op_gemm_group_accumulate(probs, k, bs if with_bsum else None)
+    b.chimera_op_gemm_group_accumulate(probs, k, bs if with_bsum else None)
     torch.cuda.synchronize()
     for i, (_, _, c) in enumerate(probs):
         assert_close(to_np(c) - c0s[i], 2 * want[i], b.BF16, "product %d" % i)
+        if bs[i] is not None:
+            assert_close(to_np(bs[i]) - bs0[i], 2 * want_b[i], b.BF16, "column sums %d" % i)
 
 
 def test_gemm_group_matches_single_launches_bitwise():
@@ -249,3 +257,18 @@ def test_attention(dtype, impl, causal, batch, seq, heads, d):
     got = to_np(dqkv)
     for name, lo in (("dq", 0), ("dk", H), ("dv", 2 * H)):
         assert_close(got[:, lo:lo + H], dqkv64[:, lo:lo + H], dtype, name)
+
+
+def test_measured_ceiling_probes():
+    import torch
+    sink = torch.zeros(1, device="cuda")
+    tf = b.chimera_probe_mfma_bf16(sink, 500)
+    assert 200.0 < tf < 2600.0, tf              # below the published dense bf16 peak, far above vector rates
+    assert float(sink.item()) == 0.0
+    src = torch.arange(1 << 22, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    gbs = b.chimera_probe_copy(src, dst)
+    assert torch.equal(src, dst)
+    assert 100.0 < gbs < 8200.0, gbs
+    with pytest.raises(b.ChimeraError):
+        b.chimera_probe_copy(src[1:], dst[1:])    # 4-byte offset: not 16-byte aligned
