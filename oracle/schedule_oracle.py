@@ -19,6 +19,19 @@ What it follows (Chimera paper, Li & Hoefler, SC'21):
 * Section 2 "Bubbles in the pipeline" and Table 2: GPipe injects all N
   forwards and then runs all backwards; DAPPLE is 1F1B with a flush.
 * Section 3.4: the critical path counts C_f, C_b.
+* Section 3.5, forward doubling and backward halving: the order of the basic
+  unit is kept, but every forward carries two micro-batches (doubling) or every
+  backward is cut into two halves of a micro-batch (halving), so that one
+  forward and one backward chunk cost about the same; a backward chunk only
+  waits for the same chunk at the next stage.  The paper's figure for it is
+  missing from the text; the reading here (basic-unit order, chunk-granular
+  backward dependencies, as-soon-as-possible replay) reproduces the number the
+  text does give: D-2 bubbles in all, D/2-1 among the forwards and D/2-1 among
+  the backwards.
+* Section 3.6 and Table 3, 2f pipelines: f down and f up pipelines, each with
+  D/(2f) micro-batches per unit under 1F1B; down pipeline i puts stage 0 on
+  worker i*(D/f) and the following stages on the following workers (cyclically);
+  up pipeline i uses the reverse order of down pipeline i.
 
 The paper has no listing for the merge; it describes it with a (missing)
 figure.  The construction here fills an explicit worker x slot grid:
@@ -51,8 +64,10 @@ number of intermediate bubbles of direct concatenation when a backward costs
 two forwards.
 """
 
-F, B = 0, 1          # op kind
-DOWN, UP = 0, 1      # pipeline
+F, B = 0, 1          # op kind: forward / backward of one micro-batch
+F2 = 2               # forward of the two micro-batches g and g+1 together (forward doubling)
+BH0, BH1 = 3, 4      # backward of the first / second half of micro-batch g (backward halving)
+DOWN, UP = 0, 1      # pipeline; with 2f pipelines: pipe = 2*i (down pipeline i) or 2*i+1 (up pipeline i)
 
 
 def one_f_one_b_order(D, n, s):
@@ -98,33 +113,92 @@ def _pipeline_table(D, n):
     return slot
 
 
-def chimera_grid(D, N):
+def worker_of(D, f, pipe, s):
+    """Worker that holds stage s of pipeline `pipe` (section 3.1; section 3.6 for f > 1)."""
+    first = (pipe // 2) * (D // f)              # worker of stage 0 of the down pipeline
+    if pipe % 2 == DOWN:
+        return (first + s) % D
+    return (first + D - 1 - s) % D              # the down pipeline's order, reversed
+
+
+def chimera_grid(D, N, f=1):
     """Overlay of all pipelines and units: list over workers of {slot: op}.
 
-    op = (kind, pipe, global_micro_batch, stage).
+    op = (kind, pipe, global_micro_batch, stage).  f down and f up pipelines;
+    inside a unit the pipelines take consecutive blocks of D/(2f) micro-batch
+    ids in the order down 0 .. down f-1, up 0 .. up f-1.
     """
     if D < 2 or D % 2:
         raise ValueError("Chimera needs an even number of stages")
     if N < D or N % D:
         raise ValueError("N must be a positive multiple of D")
-    n = D // 2
+    if f < 1 or (D // 2) % f:
+        raise ValueError("f must divide D/2")
+    n = D // (2 * f)
     table = _pipeline_table(D, n)
     grid = [dict() for _ in range(D)]
     for k in range(N // D):
-        for pipe in (DOWN, UP):
-            for (kind, m, s), t in table.items():
-                w = s if pipe == DOWN else D - 1 - s
-                g = k * D + (m if pipe == DOWN else n + m)
-                cell = 2 * D * k + t
-                if cell in grid[w]:
-                    raise AssertionError("merge conflict on worker %d slot %d" % (w, cell))
-                grid[w][cell] = (kind, pipe, g, s)
+        for i in range(f):
+            for direction in (DOWN, UP):
+                pipe = 2 * i + direction
+                block = i if direction == DOWN else f + i
+                for (kind, m, s), t in table.items():
+                    w = worker_of(D, f, pipe, s)
+                    g = k * D + block * n + m
+                    cell = 2 * D * k + t
+                    if cell in grid[w]:
+                        raise AssertionError("merge conflict on worker %d slot %d" % (w, cell))
+                    grid[w][cell] = (kind, pipe, g, s)
     return grid
 
 
-def chimera_schedule(D, N):
+def chimera_schedule(D, N, f=1):
     """Per-worker op lists [(kind, pipe, mb, stage), ...] in execution order."""
-    return [[row[t] for t in sorted(row)] for row in chimera_grid(D, N)]
+    return [[row[t] for t in sorted(row)] for row in chimera_grid(D, N, f)]
+
+
+def forward_doubling_schedule(D, N):
+    """Section 3.5, forward doubling: units of 2D micro-batches.
+
+    The order is that of the direct schedule for N/2 "double" micro-batches;
+    the forward of double micro-batch j becomes one forward over micro-batches
+    2j and 2j+1, its backward becomes the backward of 2j followed by that of
+    2j+1 (each with recomputation when the runtime drops the activations).
+    If N/D is odd the last D micro-batches form an ordinary basic unit.
+    """
+    if N < 2 * D or N % D:
+        raise ValueError("forward doubling needs N = K*D with K >= 2")
+    K = N // D
+    lists = [[] for _ in range(D)]
+    doubled = chimera_schedule(D, (K // 2) * D)
+    for w, ops in enumerate(doubled):
+        for kind, pipe, j, st in ops:
+            if kind == F:
+                lists[w].append((F2, pipe, 2 * j, st))
+            else:
+                lists[w] += [(B, pipe, 2 * j, st), (B, pipe, 2 * j + 1, st)]
+    if K % 2:
+        rest = chimera_schedule(D, D)
+        for w, ops in enumerate(rest):
+            lists[w] += [(kind, pipe, (K - 1) * D + g, st) for kind, pipe, g, st in ops]
+    return lists
+
+
+def backward_halving_schedule(D, N):
+    """Section 3.5, backward halving: the same schedule as forward doubling, but
+    a forward keeps one micro-batch and a backward is cut into two halves."""
+    if N < D or N % D:
+        raise ValueError("N must be a positive multiple of D")
+    lists = []
+    for ops in chimera_schedule(D, N):
+        l = []
+        for kind, pipe, g, st in ops:
+            if kind == F:
+                l.append((F, pipe, g, st))
+            else:
+                l += [(BH0, pipe, g, st), (BH1, pipe, g, st)]
+        lists.append(l)
+    return lists
 
 
 def gpipe_schedule(D, N):
@@ -143,22 +217,30 @@ def one_f_one_b_schedule(D, N):
             for s in range(D)]
 
 
-def simulate(lists, D, cost_f=1, cost_b=1):
+def simulate(lists, D, cost_f=1, cost_b=1, cost_f2=None, cost_bh=None):
     """ASAP replay of per-worker op lists under the pipeline's data dependencies.
 
     Dependencies of a micro-batch g: forward at stage s needs forward at s-1;
     backward at the last stage needs the forward there; backward at stage s
-    needs backward at s+1.  A worker runs its list strictly in order, one op at
-    a time.  Returns a dict with
+    needs backward at s+1.  A doubled forward (F2, micro-batches g and g+1)
+    chains like a forward; the backward of g or g+1 at the last stage needs it.
+    A half backward chains with the same half at the next stage.  A worker
+    runs its list strictly in order, one op at a time.  cost_f2 (default
+    cost_b) and cost_bh (default cost_f) price the doubled forward and the half
+    backward.  Returns a dict with
       start[w][i], finish[w][i]   per op,
       makespan,
       bubbles[w]   = makespan - busy time of worker w,
-      stash_peak[w] = max over time of (#forwards - #backwards) run so far,
+      stash_peak[w] = max over time of the micro-batches whose activations the
+                      worker holds (forward +1, doubled forward +2, backward
+                      -1, half backward -1/2; no recomputation assumed),
       critical     = (C_f, C_b): forwards and backwards on the chain of ops
                      that fixes the makespan (section 3.4).
     """
     W = len(lists)
-    cost = {F: cost_f, B: cost_b}
+    cost = {F: cost_f, B: cost_b, F2: cost_b if cost_f2 is None else cost_f2,
+            BH0: cost_f if cost_bh is None else cost_bh, BH1: cost_f if cost_bh is None else cost_bh}
+    live_change = {F: 2, F2: 4, B: -2, BH0: -1, BH1: -1}      # in half micro-batches
     where = {}
     for w, ops in enumerate(lists):
         for i, (kind, pipe, g, s) in enumerate(ops):
@@ -167,9 +249,13 @@ def simulate(lists, D, cost_f=1, cost_b=1):
             where[key] = (w, i)
 
     def dependency(kind, g, s):
-        if kind == F:
-            return (F, g, s - 1) if s > 0 else None
-        return (B, g, s + 1) if s < D - 1 else (F, g, s)
+        if kind in (F, F2):
+            return (kind, g, s - 1) if s > 0 else None
+        if s < D - 1:
+            return (kind, g, s + 1)
+        if (F, g, s) in where:
+            return (F, g, s)
+        return (F2, g - g % 2, s)                # the doubled forward that carried g
 
     start = [[None] * len(ops) for ops in lists]
     finish = [[None] * len(ops) for ops in lists]
@@ -217,10 +303,10 @@ def simulate(lists, D, cost_f=1, cost_b=1):
         bubbles.append(makespan - busy)
         live = peak = 0
         for kind, _, _, _ in ops:
-            live += 1 if kind == F else -1
+            live += live_change[kind]
             assert live >= 0, "backward before forward"
             peak = max(peak, live)
-        peaks.append(peak)
+        peaks.append(peak // 2 if peak % 2 == 0 else peak / 2)
 
     # critical path: walk back from the op that ends last (lowest worker wins ties)
     end = min((w for w in range(W) if finish[w] and finish[w][-1] == makespan))
@@ -228,7 +314,7 @@ def simulate(lists, D, cost_f=1, cost_b=1):
     cf = cb = 0
     while node is not None:
         w, i = node
-        if lists[w][i][0] == F:
+        if lists[w][i][0] in (F, F2):
             cf += 1
         else:
             cb += 1

@@ -158,3 +158,144 @@ def test_simulator_detects_broken_order():
     bad[3][2], bad[3][3] = bad[3][3], bad[3][2]     # B0d before F0d on the last stage
     with pytest.raises(AssertionError):
         so.check_valid(bad, 4, 4, 2)
+
+
+# ------------------------------------------------- generalisations (sections 3.5, 3.6)
+def _gen_pins():
+    out = []
+    with open(os.path.join(HERE, "golden", "paper_generalisation_pins.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if line:
+                out.append((line[0],) + tuple(int(v) for v in line[1:]))
+    return out
+
+
+def _idle_before_first_backward(lists, r, w):
+    """Idle slots of worker w before its first backward chunk starts (unit slots)."""
+    first_b = next(i for i, op in enumerate(lists[w]) if op[0] not in (so.F, so.F2))
+    return r["start"][w][first_b] - first_b
+
+
+@pytest.mark.parametrize("pin", _gen_pins(), ids=lambda p: "-".join(map(str, p)))
+def test_paper_generalisation_pins(pin):
+    key, D, N, f, want = pin
+    if key.endswith("_2f"):
+        lists = so.chimera_schedule(D, N, f)
+        r = so.simulate(lists, D, 1, 1)
+        if key == "bubbles_2f":
+            assert r["bubbles"] == [want] * D
+            # Table 3's ratio (D-2f)/(2fN+D-2f) is bubbles / makespan
+            assert r["bubbles"][0] * (2 * f * N + D - 2 * f) == (D - 2 * f) * r["makespan"]
+        elif key == "stash_min_2f":
+            assert min(r["stash_peak"]) == want
+        else:
+            assert max(r["stash_peak"]) == want
+    elif key.startswith("worker_down1_stage"):
+        assert so.worker_of(D, f, 2, int(key[len("worker_down1_stage"):])) == want
+    else:
+        doubling = key.endswith("doubling")
+        lists = so.forward_doubling_schedule(D, N) if doubling else so.backward_halving_schedule(D, N)
+        r = so.simulate(lists, D, 1, 1, cost_f2=1, cost_bh=1)
+        if key.startswith("bubbles_fwd_part"):
+            for w in range(D):
+                assert _idle_before_first_backward(lists, r, w) == want
+                assert r["bubbles"][w] - want == D // 2 - 1
+        else:
+            assert r["bubbles"] == [want] * D
+
+
+@pytest.mark.parametrize("D,f", [(4, 1), (4, 2), (8, 2), (8, 4), (12, 2), (12, 3), (12, 6), (16, 2), (16, 4), (32, 8)])
+@pytest.mark.parametrize("K", [1, 2, 3])
+def test_2f_structure(D, f, K):
+    N = K * D
+    lists = so.chimera_schedule(D, N, f)
+    assert so.check_valid(lists, D, N, stages_per_worker=2 * f)
+    n = D // (2 * f)
+    for w, ops in enumerate(lists):
+        assert len(ops) == 2 * N
+        held = {(pipe, s) for _, pipe, _, s in ops}
+        assert held == {(pipe, s) for pipe in range(2 * f) for s in range(D) if so.worker_of(D, f, pipe, s) == w}
+        assert len(held) == 2 * f
+        for pipe in range(2 * f):
+            assert sum(1 for k, p, _, _ in ops if k == so.F and p == pipe) == K * n
+    # every pipeline visits every worker exactly once, the up pipeline in the reverse order of its down pipeline
+    for i in range(f):
+        down = [so.worker_of(D, f, 2 * i, s) for s in range(D)]
+        up = [so.worker_of(D, f, 2 * i + 1, s) for s in range(D)]
+        assert sorted(down) == list(range(D)) and up == down[::-1]
+        assert down[0] == i * (D // f)
+    r = so.simulate(lists, D, 1, 1)
+    assert r["makespan"] == 2 * N + D // f - 2
+    assert r["bubbles"] == [D // f - 2] * D
+    assert min(r["stash_peak"]) == D - D // (2 * f) + 1 and max(r["stash_peak"]) == D
+
+
+def test_2f_rejects_bad_f():
+    for D, f in [(8, 3), (8, 0), (12, 4), (6, 2)]:
+        with pytest.raises(ValueError):
+            so.chimera_schedule(D, D, f)
+
+
+def test_f1_is_the_bidirectional_schedule():
+    for D in (2, 4, 8):
+        assert so.chimera_schedule(D, 2 * D, 1) == so.chimera_schedule(D, 2 * D)
+
+
+@pytest.mark.parametrize("D", [2, 4, 6, 8, 16, 32])
+@pytest.mark.parametrize("K", [2, 3, 4, 5])
+def test_forward_doubling_structure(D, K):
+    N = K * D
+    lists = so.forward_doubling_schedule(D, N)
+    # every micro-batch: forward exactly once per stage (alone or in a pair), backward exactly once per stage
+    fwd, bwd = set(), set()
+    for w, ops in enumerate(lists):
+        assert {s for _, _, _, s in ops} == {w, D - 1 - w}
+        for kind, pipe, g, s in ops:
+            assert s == (w if pipe == so.DOWN else D - 1 - w)
+            if kind == so.F2:
+                assert g % 2 == 0
+                for gg in (g, g + 1):
+                    assert (gg, s) not in fwd
+                    fwd.add((gg, s))
+            elif kind == so.F:
+                assert (g, s) not in fwd
+                fwd.add((g, s))
+            else:
+                assert kind == so.B and (g, s) in fwd and (g, s) not in bwd
+                bwd.add((g, s))
+    want = {(g, s) for g in range(N) for s in range(D)}
+    assert fwd == want and bwd == want
+    r = so.simulate(lists, D, 1, 1, cost_f2=1)
+    # whole doubled units (1 slot per doubled forward, 1 per backward): 3D busy slots per unit
+    if K % 2 == 0:
+        assert r["bubbles"] == [D - 2] * D
+        assert r["makespan"] == 3 * N // 2 + D - 2
+        # twice the activations of the basic schedule when nothing is recomputed (section 3.5)
+        base = so.simulate(so.chimera_schedule(D, D), D)["stash_peak"]
+        assert r["stash_peak"] == [2 * p for p in base]
+
+
+@pytest.mark.parametrize("D", [2, 4, 6, 8, 16])
+@pytest.mark.parametrize("K", [1, 2, 3])
+def test_backward_halving_structure(D, K):
+    N = K * D
+    lists = so.backward_halving_schedule(D, N)
+    base = so.chimera_schedule(D, N)
+    for ops, bops in zip(lists, base):
+        # same forwards in the same order; each backward replaced by its two halves, in order
+        assert [op for op in ops if op[0] == so.F] == [op for op in bops if op[0] == so.F]
+        halves = [(op[0], op[2], op[3]) for op in ops if op[0] != so.F]
+        assert halves == [(h, g, s) for kind, _, g, s in bops if kind == so.B for h in (so.BH0, so.BH1)]
+    r = so.simulate(lists, D, 1, 1, cost_bh=1)
+    assert r["bubbles"] == [D - 2] * D
+    # no more activations than the basic schedule (section 3.5)
+    assert r["stash_peak"] == so.simulate(base, D)["stash_peak"]
+
+
+def test_halving_with_true_costs_matches_direct():
+    # a half backward costing half a backward: the replay is never slower than the direct schedule
+    for D in (4, 8):
+        direct = so.simulate(so.chimera_schedule(D, D), D, 2, 4)["makespan"]
+        halved = so.simulate(so.backward_halving_schedule(D, D), D, 2, 4, cost_bh=2)["makespan"]
+        assert halved <= direct
