@@ -62,7 +62,23 @@ enum {
 enum { CHIMERA_F32 = 0, CHIMERA_BF16 = 1 };
 
 /* schedule algorithms */
-enum { CHIMERA_DIRECT = 0, CHIMERA_GPIPE = 1, CHIMERA_1F1B = 2 };
+enum {
+    CHIMERA_DIRECT = 0,   /* Chimera, direct concatenation of basic units (sections 3.1, 3.5) */
+    CHIMERA_GPIPE = 1,
+    CHIMERA_1F1B = 2,
+    CHIMERA_DOUBLING = 3, /* Chimera with forward doubling (section 3.5)                      */
+    CHIMERA_HALVING = 4   /* Chimera with backward halving (section 3.5)                      */
+};
+
+/* op kinds of a schedule */
+enum {
+    CHIMERA_OP_F = 0,     /* forward of micro-batch mb                                          */
+    CHIMERA_OP_B = 1,     /* backward of micro-batch mb                                         */
+    CHIMERA_OP_F2 = 2,    /* forward of micro-batches mb and mb+1 together (mb even)            */
+    CHIMERA_OP_BH0 = 3,   /* backward of the first half of micro-batch mb's sequences           */
+    CHIMERA_OP_BH1 = 4,   /* backward of the second half                                        */
+    CHIMERA_OP_KINDS = 5
+};
 
 /* stage options (chimera_stage_set_option) */
 enum {
@@ -86,12 +102,14 @@ const char* chimera_last_error(void);
  * (section 2, "Bubbles in the pipeline").  Pure CPU; usable without a GPU.
  */
 typedef struct {
-    int32_t kind;   /* 0 = forward, 1 = backward                               */
-    int32_t pipe;   /* 0 = down pipeline, 1 = up pipeline (baselines: always 0) */
+    int32_t kind;   /* CHIMERA_OP_*: 0 = forward, 1 = backward, ...              */
+    int32_t pipe;   /* 0 = down pipeline, 1 = up pipeline (baselines: always 0); */
+                    /* with 2f pipelines 2i = down pipeline i, 2i+1 = up pipeline i */
     int32_t mb;     /* global micro-batch id, 0 .. N-1                          */
     int32_t stage;  /* pipeline stage the op belongs to                         */
     int32_t slot;   /* activation-stash slot of that stage used by this         */
-                    /* micro-batch (lowest free slot at its forward)            */
+                    /* micro-batch (lowest free slot at its forward); -1 for a  */
+                    /* doubled forward and the backwards that recompute after it */
     int32_t start;  /* start time when all workers replay as soon as possible   */
                     /* with forward cost = backward cost = 1                    */
     int32_t last_of_stage; /* 1 on the backward that completes this stage's     */
@@ -113,6 +131,45 @@ int chimera_schedule(int algo, int D, int N, int rank,
 int chimera_schedule_stats(int algo, int D, int N, int cost_f, int cost_b,
                            int64_t* h_makespan, int64_t* h_bubbles,
                            int32_t* h_stash_peak, int32_t* h_critical);
+
+/* The same for 2f pipelines (section 3.6, Table 3): algo CHIMERA_DIRECT with f down and f up
+ * pipelines, f a divisor of D/2 (f = 1 is the call above); other algorithms need f = 1.
+ * CHIMERA_DOUBLING needs N = K*D with K >= 2: units of 2D micro-batches, every forward
+ * carries two micro-batches (kind F2), every backward one; an odd K leaves one ordinary
+ * unit at the end.  CHIMERA_HALVING: the direct order with every backward cut in two
+ * halves (kinds BH0, BH1).  Count: 2N ops; 3N for halving; for doubling 3 ops per pair
+ * of micro-batches in the doubled units and 2 per micro-batch in an ordinary unit. */
+int chimera_schedule_pipes(int algo, int D, int N, int f, int rank,
+                           chimera_op* h_out, size_t cap, size_t* h_count);
+
+/* Replay statistics with one integer cost (>= 1) per op kind, h_cost[CHIMERA_OP_KINDS].
+ * h_stash_peak_halves[D]: most activations a worker holds, in HALF micro-batches
+ * (forward +2, doubled forward +4, backward -2, half backward -1; no recomputation).
+ * The paper's figures: Table 3 (bubble ratio (D-2f)/(2fN+D-2f), activations
+ * [(D-D/2f+1) M_a, D M_a]); section 3.5 (D-2 bubbles for doubling and halving). */
+int chimera_schedule_stats_costs(int algo, int D, int N, int f, const int64_t* h_cost,
+                                 int64_t* h_makespan, int64_t* h_bubbles,
+                                 int32_t* h_stash_peak_halves, int32_t* h_critical);
+
+/* Worker that holds `stage` of pipeline `pipe` (section 3.1; section 3.6 for f > 1):
+ * down pipeline i starts on worker i*(D/f) and walks upwards cyclically, up pipeline i
+ * uses the reverse order.  Returns the worker (>= 0) or EINVAL. */
+int chimera_pipe_worker(int D, int f, int pipe, int stage);
+
+/* Performance model, Eq. (1) of section 3.4:
+ *   T = (F_t + Comm_p2p) C_f + (B_t + Comm_p2p) C_b + max_i Comm_unoverlapped(i),
+ * Comm_p2p = alpha + beta*act_words, Comm_allreduce = 2 log2(r) alpha + 2 (r-1) beta
+ * grad_words / r with r = 2 f W stage replicas for Chimera and W for GPipe / 1F1B.
+ * C_f, C_b come from the as-soon-as-possible replay of the schedule with those op costs.
+ * Free regions are a worker's idle intervals: the allreduce of a stage uses the idle time
+ * after the stage's last backward (eager != 0) or after the worker's last op (eager == 0),
+ * a worker's allreduces run one after the other, and what is left at the end of the
+ * computation is unoverlapped.  f_t, b_t in seconds (any unit, consistently), alpha in the
+ * same unit, beta in that unit per word.  h_out[7] = {T, F_t C_f + B_t C_b, (C_f + C_b)
+ * Comm_p2p, Comm_allreduce, max_i Comm_unoverlapped(i), C_f, C_b}.  Pure CPU. */
+int chimera_model_iteration_time(int algo, int D, int N, int f, int W, double f_t, double b_t,
+                                 double alpha, double beta, double act_words, double grad_words,
+                                 int eager, double* h_out);
 
 /* --------------------------------------------------------------------- stage
  * A stage = `layers` Transformer blocks at fixed shape (the paper's F_t / B_t

@@ -9,7 +9,8 @@ LIB_PATH = os.path.join(HERE, "libchimera.so")
 
 OK, EINVAL, ENOMEM, ESTATE, EDEVICE = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
-DIRECT, GPIPE, ONE_F_ONE_B = 0, 1, 2
+DIRECT, GPIPE, ONE_F_ONE_B, DOUBLING, HALVING = 0, 1, 2, 3, 4
+OP_F, OP_B, OP_F2, OP_BH0, OP_BH1 = 0, 1, 2, 3, 4
 OPT_CAUSAL, OPT_GELU, OPT_KERNELS, OPT_OVERLAP = 0, 1, 2, 3
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL, EPI_DGELU, EPI_ACCUM_F32 = range(6)
 
@@ -34,6 +35,11 @@ _SIGNATURES = {
     "chimera_schedule": (_i, [_i, _i, _i, _i, C.POINTER(chimera_op), _sz, C.POINTER(_sz)]),
     "chimera_schedule_stats": (_i, [_i, _i, _i, _i, _i, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                     C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "chimera_schedule_pipes": (_i, [_i, _i, _i, _i, _i, C.POINTER(chimera_op), _sz, C.POINTER(_sz)]),
+    "chimera_schedule_stats_costs": (_i, [_i, _i, _i, _i, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                          C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "chimera_pipe_worker": (_i, [_i, _i, _i, _i]),
+    "chimera_model_iteration_time": (_i, [_i, _i, _i, _i, _i] + [C.c_double] * 6 + [_i, C.POINTER(C.c_double)]),
     "chimera_stage_create": (_p, [_i] * 6),
     "chimera_stage_set_option": (_i, [_p, _i, _i]),
     "chimera_stage_destroy": (None, [_p]),
@@ -106,6 +112,38 @@ def chimera_schedule(algo, D, N, rank):
     buf = (chimera_op * cap)()
     check(lib().chimera_schedule(algo, D, N, rank, buf, cap, C.byref(n)))
     return list(buf[:n.value])
+
+
+def chimera_schedule_pipes(algo, D, N, f, rank):
+    n = _sz(0)
+    cap = 3 * max(N, 1)
+    buf = (chimera_op * cap)()
+    check(lib().chimera_schedule_pipes(algo, D, N, f, rank, buf, cap, C.byref(n)))
+    return list(buf[:n.value])
+
+
+def chimera_schedule_stats_costs(algo, D, N, f, costs):
+    """costs: one integer per op kind (F, B, F2, BH0, BH1)."""
+    mk = C.c_int64(0)
+    bub = (C.c_int64 * max(D, 1))()
+    peak = (C.c_int32 * max(D, 1))()
+    crit = (C.c_int32 * 2)()
+    check(lib().chimera_schedule_stats_costs(algo, D, N, f, (C.c_int64 * 5)(*costs), C.byref(mk), bub, peak, crit))
+    return {"makespan": mk.value, "bubbles": list(bub[:D]), "stash_peak_halves": list(peak[:D]), "critical": (crit[0], crit[1])}
+
+
+def chimera_pipe_worker(D, f, pipe, stage):
+    w = lib().chimera_pipe_worker(D, f, pipe, stage)
+    if w < 0:
+        check(w)
+    return w
+
+
+def chimera_model_iteration_time(algo, D, N, f, W, f_t, b_t, alpha, beta, act_words, grad_words, eager=True):
+    out = (C.c_double * 7)()
+    check(lib().chimera_model_iteration_time(algo, D, N, f, W, f_t, b_t, alpha, beta, act_words, grad_words, int(eager), out))
+    return {"T": out[0], "compute": out[1], "p2p": out[2], "allreduce": out[3], "unoverlapped": out[4],
+            "c_f": int(out[5]), "c_b": int(out[6])}
 
 
 def chimera_schedule_stats(algo, D, N, cost_f=1, cost_b=1):

@@ -21,8 +21,18 @@ struct ReplayStats {
     std::vector<int32_t> stash_peak;
     int32_t cf = 0, cb = 0;
 };
+template <typename T> struct ReplayStatsT {
+    T makespan = 0;
+    std::vector<T> bubbles;
+    std::vector<int32_t> stash_peak_halves;      // most activations held, in half micro-batches
+    int32_t cf = 0, cb = 0;
+};
+struct ModelResult { double T, compute, p2p, allreduce, unoverlapped; int c_f, c_b; };
 
 int build_schedule(int algo, int D, int N, std::vector<std::vector<Op>>& lists);
+int build_schedule(int algo, int D, int N, int f, std::vector<std::vector<Op>>& lists);
+int model_iteration(int algo, int D, int N, int f, int W, double f_t, double b_t, double alpha, double beta,
+                    double act_words, double grad_words, int eager, ModelResult* out);
 int replay(const std::vector<std::vector<Op>>& lists, int D, int N, int64_t cost_f, int64_t cost_b,
            std::vector<std::vector<int64_t>>& start, ReplayStats* stats);
 int annotate(std::vector<std::vector<Op>>& lists, int D, int N);

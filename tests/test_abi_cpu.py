@@ -129,3 +129,141 @@ def test_stage_create_errors_and_sizes():
     assert L.chimera_stage_weight_bytes(st16) == 2 * per_layer * 2
     assert L.chimera_stage_grad_bytes(st16) == 2 * per_layer * 4
     L.chimera_stage_destroy(st16)
+
+
+# ------------------------------------------------------------ sections 3.5, 3.6, 3.4
+from oracle import perf_model_oracle as pm   # noqa: E402
+
+
+@pytest.mark.parametrize("D,f", [(4, 1), (4, 2), (8, 2), (8, 4), (12, 2), (12, 3), (16, 4), (32, 8), (32, 16)])
+@pytest.mark.parametrize("K", [1, 2, 3])
+def test_2f_schedule_bit_exact(D, f, K):
+    N = K * D
+    want = so.chimera_schedule(D, N, f)
+    ref = so.simulate(want, D, 1, 1)
+    for rank in range(D):
+        got = b.chimera_schedule_pipes(b.DIRECT, D, N, f, rank)
+        assert [o.astuple() for o in got] == want[rank]
+        assert [o.start for o in got] == ref["start"][rank]
+        live = {}
+        for o in got:
+            key = (o.pipe, o.slot)
+            if o.kind == b.OP_F:
+                assert key not in live
+                live[key] = o.mb
+            else:
+                assert live.pop(key) == o.mb
+        assert not live
+    for costs in ((1, 1, 1, 1, 1), (1, 2, 2, 1, 1), (3, 7, 7, 3, 3)):
+        ref = so.simulate(want, D, costs[0], costs[1])
+        got = b.chimera_schedule_stats_costs(b.DIRECT, D, N, f, costs)
+        assert got["makespan"] == ref["makespan"] and got["bubbles"] == ref["bubbles"]
+        assert got["stash_peak_halves"] == [2 * p for p in ref["stash_peak"]]
+        assert got["critical"] == ref["critical"]
+    for pipe in range(2 * f):
+        for s in range(D):
+            assert b.chimera_pipe_worker(D, f, pipe, s) == so.worker_of(D, f, pipe, s)
+
+
+@pytest.mark.parametrize("D", [2, 4, 6, 8, 16, 32])
+@pytest.mark.parametrize("K", [2, 3, 4, 5])
+def test_doubling_schedule_bit_exact(D, K):
+    N = K * D
+    want = so.forward_doubling_schedule(D, N)
+    for costs in ((1, 1, 1, 1, 1), (1, 3, 2, 1, 1), (2, 5, 4, 3, 3)):
+        ref = so.simulate(want, D, costs[0], costs[1], cost_f2=costs[2], cost_bh=costs[3])
+        got = b.chimera_schedule_stats_costs(b.DOUBLING, D, N, 1, costs)
+        assert got["makespan"] == ref["makespan"] and got["bubbles"] == ref["bubbles"]
+        assert got["stash_peak_halves"] == [int(2 * p) for p in ref["stash_peak"]]
+        assert got["critical"] == ref["critical"]
+    ref = so.simulate(want, D, 1, 1, cost_f2=1)
+    for rank in range(D):
+        got = b.chimera_schedule_pipes(b.DOUBLING, D, N, 1, rank)
+        assert [o.astuple() for o in got] == want[rank]
+        assert [o.start for o in got] == ref["start"][rank]
+        assert got == got and b.chimera_schedule(b.DOUBLING, D, N, rank)[0].astuple() == want[rank][0]
+        for o in got:
+            if o.kind == b.OP_F2 or (o.kind == b.OP_B and o.mb < (K // 2) * 2 * D):
+                assert o.slot == -1
+            else:
+                assert o.slot >= 0
+
+
+@pytest.mark.parametrize("D", [2, 4, 8, 16])
+@pytest.mark.parametrize("K", [1, 2, 3])
+def test_halving_schedule_bit_exact(D, K):
+    N = K * D
+    want = so.backward_halving_schedule(D, N)
+    for costs in ((1, 1, 1, 1, 1), (2, 4, 4, 2, 2), (2, 5, 4, 3, 3)):
+        ref = so.simulate(want, D, costs[0], costs[1], cost_f2=costs[2], cost_bh=costs[3])
+        got = b.chimera_schedule_stats_costs(b.HALVING, D, N, 1, costs)
+        assert got["makespan"] == ref["makespan"] and got["bubbles"] == ref["bubbles"]
+        assert got["stash_peak_halves"] == [int(round(2 * p)) for p in ref["stash_peak"]]
+        assert got["critical"] == ref["critical"]
+    ref = so.simulate(want, D, 1, 1, cost_bh=1)
+    for rank in range(D):
+        got = b.chimera_schedule_pipes(b.HALVING, D, N, 1, rank)
+        assert [o.astuple() for o in got] == want[rank]
+        assert [o.start for o in got] == ref["start"][rank]
+        # the two halves of a backward share the slot its forward took; the second frees it
+        live = {}
+        for o in got:
+            key = (o.pipe, o.slot)
+            if o.kind == b.OP_F:
+                assert key not in live
+                live[key] = o.mb
+            elif o.kind == b.OP_BH0:
+                assert live[key] == o.mb
+            else:
+                assert o.kind == b.OP_BH1 and live.pop(key) == o.mb
+        assert not live
+
+
+@pytest.mark.parametrize("args", [
+    (b.DIRECT, 8, 8, 3, 0), (b.DIRECT, 8, 8, 0, 0), (b.GPIPE, 8, 8, 2, 0), (b.DOUBLING, 4, 4, 1, 0),
+    (b.DOUBLING, 4, 10, 1, 0), (b.HALVING, 5, 5, 1, 0), (b.DIRECT, 8, 8, 2, 8), (7, 4, 4, 1, 0)])
+def test_schedule_pipes_errors(args):
+    with pytest.raises(b.ChimeraError) as e:
+        b.chimera_schedule_pipes(*args)
+    assert e.value.code == b.EINVAL
+
+
+def test_pipe_worker_errors():
+    for args in ((8, 3, 0, 0), (8, 2, 4, 0), (8, 2, 0, 8), (7, 1, 0, 0)):
+        with pytest.raises(b.ChimeraError):
+            b.chimera_pipe_worker(*args)
+
+
+MODEL_CASES = [
+    # algo, oracle lists, D, N, f, replicas per group
+    (b.DIRECT, lambda: so.chimera_schedule(6, 6), 6, 6, 1, 2),
+    (b.DIRECT, lambda: so.chimera_schedule(8, 16), 8, 16, 1, 2),
+    (b.DIRECT, lambda: so.chimera_schedule(8, 8, 2), 8, 8, 2, 4),
+    (b.DIRECT, lambda: so.chimera_schedule(16, 32, 4), 16, 32, 4, 8),
+    (b.ONE_F_ONE_B, lambda: so.one_f_one_b_schedule(8, 8), 8, 8, 1, 1),
+    (b.GPIPE, lambda: so.gpipe_schedule(4, 12), 4, 12, 1, 1),
+]
+
+
+@pytest.mark.parametrize("algo,make,D,N,f,rep", MODEL_CASES)
+@pytest.mark.parametrize("eager", [True, False])
+def test_performance_model_matches_oracle(algo, make, D, N, f, rep, eager):
+    lists = make()
+    for W, f_t, b_t, alpha, beta, act, grad in [
+            (1, 1.0, 2.0, 0.0, 0.0, 0.0, 0.0), (4, 3.1e-3, 5.7e-3, 6e-6, 2.6e-11, 4.2e6, 1.5e8),
+            (2, 1.0e-3, 3.0e-3, 1e-4, 1e-9, 1.0e5, 5.0e7), (8, 2.0, 4.0, 0.5, 1e-7, 1.0e6, 3.0e7)]:
+        want = pm.iteration_time(lists, D, W, f_t, b_t, alpha, beta, act, grad, rep, eager)
+        got = b.chimera_model_iteration_time(algo, D, N, f, W, f_t, b_t, alpha, beta, act, grad, eager)
+        assert (got["c_f"], got["c_b"]) == (want["c_f"], want["c_b"])
+        for key in ("T", "compute", "p2p", "allreduce"):
+            assert got[key] == pytest.approx(want[key], rel=1e-12, abs=1e-15), key
+        assert got["unoverlapped"] == pytest.approx(max(want["unoverlapped"]), rel=1e-12, abs=1e-12)
+
+
+def test_performance_model_paper_example_and_errors():
+    r = b.chimera_model_iteration_time(b.DIRECT, 6, 6, 1, 1, 1.0, 2.0, 0.0, 0.0, 0.0, 0.0)
+    assert (r["c_f"], r["c_b"], r["T"]) == (6, 10, 26.0)          # section 3.4
+    for bad in ((b.DIRECT, 6, 6, 1, 0, 1.0, 2.0, 0.0, 0.0, 0.0, 0.0), (b.DIRECT, 6, 6, 1, 1, 0.0, 2.0, 0.0, 0.0, 0.0, 0.0),
+                (b.DIRECT, 6, 6, 1, 1, 1.0, 2.0, -1.0, 0.0, 0.0, 0.0), (b.DOUBLING, 4, 8, 1, 1, 1.0, 2.0, 0.0, 0.0, 0.0, 0.0)):
+        with pytest.raises(b.ChimeraError):
+            b.chimera_model_iteration_time(*bad)
