@@ -86,9 +86,14 @@ enum {
     CHIMERA_OPT_GELU = 1,    /* 0 (default) = tanh form, 1 = exact erf form         */
     CHIMERA_OPT_KERNELS = 2, /* 0 (default) = matrix-core kernels where the shape   */
                              /* allows, 1 = plain reference kernels everywhere      */
-    CHIMERA_OPT_OVERLAP = 3  /* 1 (default) = weight and bias gradients of a        */
+    CHIMERA_OPT_OVERLAP = 3, /* 1 (default) = weight and bias gradients of a        */
                              /* backward run on a second stream of the stage's own, */
                              /* beside the input-gradient chain; 0 = one stream     */
+    CHIMERA_OPT_KEEP = 4     /* 1 (default) = a forward keeps its activations for   */
+                             /* the backward; 0 = forward-only stage that keeps     */
+                             /* nothing (activation recomputation, section 3.5): one */
+                             /* scratch slot of at most two blocks, chimera_bwd is   */
+                             /* ESTATE, chimera_stage_stash_slot_bytes shrinks       */
 };
 
 typedef struct chimera_stage chimera_stage;
@@ -214,6 +219,12 @@ int chimera_fwd_slot(chimera_stage* st, int mb, int slot);
  * parameter gradients to d_grads (float accumulation in call order), frees
  * the slot.  ESTATE: forward of mb not done. */
 int chimera_bwd(chimera_stage* st, int mb);
+/* Backward halving (section 3.5): the backward of micro-batch mb in two parts, half 0 =
+ * its first microbatch/2 sequences, half 1 = the rest, each a backward at half the
+ * micro-batch size over the same stash slot; the two calls together add exactly the
+ * gradients chimera_bwd(mb) would add and write the same dx.  Half 0 must come first;
+ * half 1 frees the slot.  EINVAL if microbatch is odd; ESTATE when out of order. */
+int chimera_bwd_half(chimera_stage* st, int mb, int half);
 
 int chimera_stage_in_flight(const chimera_stage* st);
 int chimera_stage_zero_grads(chimera_stage* st);                 /* enqueued   */
@@ -233,6 +244,23 @@ int chimera_run_worker(int rank, int D, int N);
 /* Same for any algorithm; for the one-pipeline baselines only the down stage
  * is used and holds stage `rank`. */
 int chimera_run_worker_algo(int algo, int rank, int D, int N);
+/* 2f pipelines (section 3.6): h_stages[p] is the stage of pipeline p (2i = down pipeline i,
+ * 2i+1 = up pipeline i) that this worker holds, count = 2f.  chimera_worker_bind(d, u) is
+ * the same with count 2.  Unbinds any doubled stages. */
+int chimera_worker_bind_pipes(chimera_stage* const* h_stages, int count);
+/* Forward doubling (section 3.5): besides the worker's two stages, two forward-only stages
+ * (CHIMERA_OPT_KEEP = 0) of the same shape at TWICE the micro-batch, bound to the same
+ * weight buffers.  The io of double micro-batch (g, g+1), g even, is registered on them under
+ * id g: x and y are [2*microbatch, seq, H] (dy, dx are not used and may repeat x, y).
+ * EINVAL when shapes or weights do not match; ESTATE without a bound worker. */
+int chimera_worker_bind_doubling(chimera_stage* down2, chimera_stage* up2);
+/* Replays chimera_schedule_pipes(algo, D, N, f, rank).  Op kinds: F forward into the op's
+ * stash slot; B backward - if the micro-batch's activations were not kept (it went through a
+ * doubled forward) the forward is run again first into a free slot (activation
+ * recomputation); F2 forward of two micro-batches on the doubled stage; BH0/BH1 the two
+ * halves of a backward.  With doubling every stage needs one stash slot more than the
+ * largest slot index in its ops.  One wait per stream at the end. */
+int chimera_run_worker_pipes(int algo, int rank, int D, int N, int f);
 /* on != 0: bracket every op of the next replays with HIP events (off by default). */
 int chimera_worker_set_timing(int on);
 /* Milliseconds the last chimera_run_worker* spent in forward ops and in

@@ -254,6 +254,55 @@ def worker_iteration(rank, D, N, params_down, params_up, xs, dys, batch, seq, he
     return ys, dxs, gd, gu
 
 
+def worker_replay(ops, params_by_pipe, xs, dys, batch, seq, heads, causal=True, gelu="tanh"):
+    """Executes one worker's op list literally, op by op (sections 3.1, 3.5, 3.6).
+
+    ops: [(kind, pipe, g, stage), ...] as the schedule oracle lists them, with
+    kind 0 forward, 1 backward, 2 forward of micro-batches g and g+1 together
+    (forward doubling), 3 / 4 backward of the first / second half of the
+    micro-batch's sequences (backward halving).  params_by_pipe[pipe] are the
+    weights of the stage this worker holds for that pipeline.
+
+    A doubled forward runs the stage once on the 2*batch sequences of the two
+    micro-batches and keeps no activations; the backward of such a micro-batch
+    first runs its forward again (activation recomputation), then the
+    backward.  A half backward is the backward of those sequences alone: every
+    operation of a block acts within one sequence, so the forward of a half
+    equals the matching rows of the whole forward and is simply recomputed here
+    instead of slicing the kept activations.
+
+    Returns (ys, dxs, grads_by_pipe): ys, dxs keyed by micro-batch id.
+    """
+    params = {p: _f64(v) for p, v in params_by_pipe.items()}
+    tokens = batch * seq
+    ys, dxs, kept, grads = {}, {}, {}, {p: None for p in params}
+    for kind, pipe, g, _stage in ops:
+        p = params[pipe]
+        if kind == 0:
+            ys[g], kept[g] = stage_fwd(xs[g], p, batch, seq, heads, causal, gelu)
+        elif kind == 2:
+            y2, _ = stage_fwd(np.concatenate([xs[g], xs[g + 1]], axis=0), p, 2 * batch, seq, heads, causal, gelu)
+            ys[g], ys[g + 1] = y2[:tokens], y2[tokens:]
+        elif kind == 1:
+            caches = kept.pop(g) if g in kept else stage_fwd(xs[g], p, batch, seq, heads, causal, gelu)[1]
+            dxs[g], gr = stage_bwd(dys[g], caches, p)
+            grads[pipe] = add_grads(grads[pipe], gr)
+        elif kind in (3, 4):
+            assert batch % 2 == 0 and g in kept
+            lo = (kind - 3) * (tokens // 2)
+            rows = slice(lo, lo + tokens // 2)
+            _, caches = stage_fwd(xs[g][rows], p, batch // 2, seq, heads, causal, gelu)
+            dx_half, gr = stage_bwd(dys[g][rows], caches, p)
+            dxs.setdefault(g, np.zeros_like(np.asarray(xs[g], dtype=np.float64)))[rows] = dx_half
+            grads[pipe] = add_grads(grads[pipe], gr)
+            if kind == 4:
+                kept.pop(g)
+        else:
+            raise ValueError("unknown op kind %r" % (kind,))
+    assert not kept, "forward without backward"
+    return ys, dxs, grads
+
+
 def flatten_grads(grads):
     """Concatenate per-layer gradients in the library's flat parameter order."""
     return np.concatenate([layer[k].reshape(-1) for layer in grads for k in PARAM_ORDER])

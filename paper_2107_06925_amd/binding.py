@@ -11,7 +11,7 @@ OK, EINVAL, ENOMEM, ESTATE, EDEVICE = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
 DIRECT, GPIPE, ONE_F_ONE_B, DOUBLING, HALVING = 0, 1, 2, 3, 4
 OP_F, OP_B, OP_F2, OP_BH0, OP_BH1 = 0, 1, 2, 3, 4
-OPT_CAUSAL, OPT_GELU, OPT_KERNELS, OPT_OVERLAP = 0, 1, 2, 3
+OPT_CAUSAL, OPT_GELU, OPT_KERNELS, OPT_OVERLAP, OPT_KEEP = 0, 1, 2, 3, 4
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RESIDUAL, EPI_DGELU, EPI_ACCUM_F32 = range(6)
 
 
@@ -52,6 +52,10 @@ _SIGNATURES = {
     "chimera_fwd": (_i, [_p, _i]),
     "chimera_fwd_slot": (_i, [_p, _i, _i]),
     "chimera_bwd": (_i, [_p, _i]),
+    "chimera_bwd_half": (_i, [_p, _i, _i]),
+    "chimera_worker_bind_pipes": (_i, [_p, _i]),
+    "chimera_worker_bind_doubling": (_i, [_p, _p]),
+    "chimera_run_worker_pipes": (_i, [_i, _i, _i, _i, _i]),
     "chimera_stage_in_flight": (_i, [_p]),
     "chimera_stage_zero_grads": (_i, [_p]),
     "chimera_stage_read_grads": (_i, [_p, _p, _sz]),
@@ -164,7 +168,10 @@ class Stage:
     """Owns the device buffers (torch tensors) a chimera_stage borrows."""
 
     def __init__(self, layers, hidden, heads, seq, microbatch, dtype, causal=True, gelu_erf=False,
-                 reference_kernels=False, stash_slots=1, stream=None, device="cuda:0", overlap=True):
+                 reference_kernels=False, stash_slots=1, stream=None, device="cuda:0", overlap=True, keep=True,
+                 share_weights_of=None):
+        """keep=False: forward-only stage (activation recomputation).  share_weights_of: another
+        Stage whose weight and gradient buffers this one binds to instead of owning its own."""
         import torch
         self.torch = torch
         self.handle = lib().chimera_stage_create(layers, hidden, heads, seq, microbatch, dtype)
@@ -175,13 +182,18 @@ class Stage:
         check(lib().chimera_stage_set_option(self.handle, OPT_GELU, int(bool(gelu_erf))))
         check(lib().chimera_stage_set_option(self.handle, OPT_KERNELS, int(bool(reference_kernels))))
         check(lib().chimera_stage_set_option(self.handle, OPT_OVERLAP, int(bool(overlap))))
+        check(lib().chimera_stage_set_option(self.handle, OPT_KEEP, int(bool(keep))))
         self.tdtype = torch.float32 if dtype == F32 else torch.bfloat16
         esz = 4 if dtype == F32 else 2
         L = lib()
         dev = torch.device(device)
         self.device = dev
-        self.weights = torch.empty(L.chimera_stage_weight_bytes(self.handle) // esz, dtype=self.tdtype, device=dev)
-        self.grads = torch.zeros(L.chimera_stage_grad_bytes(self.handle) // 4, dtype=torch.float32, device=dev)
+        if share_weights_of is not None:
+            self.weights, self.grads = share_weights_of.weights, share_weights_of.grads
+            assert self.weights.numel() == L.chimera_stage_weight_bytes(self.handle) // esz
+        else:
+            self.weights = torch.empty(L.chimera_stage_weight_bytes(self.handle) // esz, dtype=self.tdtype, device=dev)
+            self.grads = torch.zeros(L.chimera_stage_grad_bytes(self.handle) // 4, dtype=torch.float32, device=dev)
         self.slot_bytes = L.chimera_stage_stash_slot_bytes(self.handle)
         self.stash = torch.empty(self.slot_bytes * stash_slots, dtype=torch.uint8, device=dev)
         self.workspace = torch.empty(L.chimera_stage_workspace_bytes(self.handle), dtype=torch.uint8, device=dev)
@@ -211,6 +223,9 @@ class Stage:
     def bwd(self, mb):
         check(lib().chimera_bwd(self.handle, mb))
 
+    def bwd_half(self, mb, half):
+        check(lib().chimera_bwd_half(self.handle, mb, half))
+
     def zero_grads(self):
         check(lib().chimera_stage_zero_grads(self.handle))
 
@@ -234,6 +249,19 @@ class Stage:
 
 def chimera_worker_bind(down, up):
     check(lib().chimera_worker_bind(down.handle, up.handle if up is not None else None))
+
+
+def chimera_worker_bind_pipes(stages):
+    arr = (C.c_void_p * len(stages))(*[None if st is None else st.handle for st in stages])
+    check(lib().chimera_worker_bind_pipes(arr, len(stages)))
+
+
+def chimera_worker_bind_doubling(down2, up2):
+    check(lib().chimera_worker_bind_doubling(down2.handle, up2.handle))
+
+
+def chimera_run_worker_pipes(algo, rank, D, N, f=1):
+    check(lib().chimera_run_worker_pipes(algo, rank, D, N, f))
 
 
 def chimera_run_worker(rank, D, N):
@@ -273,6 +301,17 @@ def chimera_profile_read():
         check(lib().chimera_profile_read(i, C.byref(ms), C.byref(n), C.byref(w)))
         out[name] = dict(ms=ms.value, launches=n.value, work=w.value)
     return out
+
+
+def stash_slots_needed_pipes(algo, D, N, f, rank):
+    """Stash slots every pipeline's stage needs on worker `rank` (index = pipeline)."""
+    ops = chimera_schedule_pipes(algo, D, N, f, rank)
+    need = [0] * (2 * f)
+    for o in ops:
+        need[o.pipe] = max(need[o.pipe], o.slot + 1)
+    if any(o.kind == OP_F2 for o in ops):
+        need = [n + 1 for n in need]              # the recomputing backwards take one more
+    return need
 
 
 def stash_slots_needed(algo, D, N, rank):

@@ -73,8 +73,11 @@ struct chimera_stage {
     int L, H, heads, S, B, dtype;
     int M, d;
     size_t esz;
-    int causal = 1, gelu_erf = 0, kernels = 0, overlap = 1;
+    int causal = 1, gelu_erf = 0, kernels = 0, overlap = 1, keep = 1;
     bool bound = false;
+    // rows (tokens) and sequences the running op works on: the whole micro-batch, or one half
+    // of it in a half backward
+    int vM = 0, vB = 0;
 
     // parameter offsets (elements) inside one block and block size
     size_t o_ln1_g, o_ln1_b, o_w_qkv, o_b_qkv, o_w_o, o_b_o, o_ln2_g, o_ln2_b, o_w_fc1, o_b_fc1, o_w_fc2, o_b_fc2;
@@ -105,6 +108,7 @@ struct chimera_stage {
     struct IO { const void* x; void* y; const void* dy; void* dx; };
     std::unordered_map<int, IO> io;
     std::unordered_map<int, int> in_flight;   // micro-batch -> slot
+    std::unordered_map<int, int> halves_done; // micro-batch -> halves of its backward already run
     std::vector<char> slot_used;
 
     const char* W(int l, size_t off) const { return weights + ((size_t)l * layer_params + off) * esz; }
@@ -141,7 +145,8 @@ void layout(chimera_stage* st) {
     st->s_g = takeb(M * 4 * H * e);
     st->s_y = takeb(M * H * re);
     st->layer_stash = b;
-    st->slot_bytes = b * st->L;
+    // a forward-only stage keeps nothing: two block areas serve as scratch in turn
+    st->slot_bytes = b * (st->keep ? st->L : std::min(st->L, 2));
 
     b = 0;
     st->w_dy[0] = takeb(M * H * e); st->w_dy[1] = takeb(M * H * e);
@@ -209,7 +214,7 @@ int wgrad_group(chimera_stage* st, const GemmArgs (&g)[4], float* const (&db)[4]
 }
 
 int attn_args(chimera_stage* st, AttnArgs& a) {
-    a.batch = st->B; a.seq = st->S; a.heads = st->heads; a.head_dim = st->d; a.causal = st->causal;
+    a.batch = st->vB; a.seq = st->S; a.heads = st->heads; a.head_dim = st->d; a.causal = st->causal;
     return 0;
 }
 
@@ -218,7 +223,7 @@ int attn_args(chimera_stage* st, AttnArgs& a) {
 // useful attention flop: 4 S^2 d per (sequence, head) forward (x 1/2 causal, exactly (S+1)/(2S)), 2x that backward
 double attn_flop(const chimera_stage* st) {
     const double c = st->causal ? (st->S + 1.0) / (2.0 * st->S) : 1.0;
-    return 4.0 * st->M * (double)st->S * st->H * c;
+    return 4.0 * st->vM * (double)st->S * st->H * c;
 }
 int st_attn_fwd(chimera_stage* st, const AttnArgs& a) {
     ProfScope prof(PC_ATTN_FWD, attn_flop(st), st->stream);
@@ -232,19 +237,19 @@ int st_attn_bwd(chimera_stage* st, const AttnArgs& a) {
 }
 // algorithmic bytes of the row-wise kernels: every operand once, at the width it is stored in
 int st_ln_fwd(chimera_stage* st, const void* x, int x_f32, const void* g, const void* b, void* y, float* mean, float* rstd) {
-    ProfScope prof(PC_LN_FWD, (double)st->M * st->H * ((x_f32 ? 4 : st->esz) + st->esz), st->stream);
-    return layernorm_fwd(st->dtype, st->M, st->H, x, x_f32, g, b, y, mean, rstd, st->stream);
+    ProfScope prof(PC_LN_FWD, (double)st->vM * st->H * ((x_f32 ? 4 : st->esz) + st->esz), st->stream);
+    return layernorm_fwd(st->dtype, st->vM, st->H, x, x_f32, g, b, y, mean, rstd, st->stream);
 }
 int st_ln_bwd(chimera_stage* st, const void* dy, const void* x, int x_f32, const float* mean, const float* rstd,
               const void* g, const void* res, int res_f32, void* dx_lo, float* dx_hi, float* dg, float* db, float* scratch) {
     const double bytes = st->esz + (x_f32 ? 4 : st->esz) + (res_f32 ? 4 : st->esz) + (dx_lo ? st->esz : 0) + (dx_hi ? 4 : 0);
-    ProfScope prof(PC_LN_BWD, (double)st->M * st->H * bytes, st->stream);
-    return layernorm_bwd(st->dtype, st->M, st->H, dy, x, x_f32, mean, rstd, g, res, res_f32, dx_lo, dx_hi, dg, db, scratch,
+    ProfScope prof(PC_LN_BWD, (double)st->vM * st->H * bytes, st->stream);
+    return layernorm_bwd(st->dtype, st->vM, st->H, dy, x, x_f32, mean, rstd, g, res, res_f32, dx_lo, dx_hi, dg, db, scratch,
                          st->stream);
 }
 int st_colsum(chimera_stage* st, int cols, const void* x, float* out, float* scratch, hipStream_t stream) {
-    ProfScope prof(PC_COLSUM, (double)st->M * cols * st->esz, stream);
-    return colsum(st->dtype, st->M, cols, x, out, scratch, stream);
+    ProfScope prof(PC_COLSUM, (double)st->vM * cols * st->esz, stream);
+    return colsum(st->dtype, st->vM, cols, x, out, scratch, stream);
 }
 
 #define HIP_TRY(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return fail(CHIMERA_EDEVICE, "%s: %s", #expr, hipGetErrorString(e__)); } while (0)
@@ -263,29 +268,32 @@ int fork_to_side(chimera_stage* st, int which) {
 // Only the stage's own input and output are in the stage dtype.
 int stage_forward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
     const int M = st->M, H = st->H, L = st->L;
+    st->vM = st->M; st->vB = st->B;
     const int wide = st->dtype == CHIMERA_BF16;       // float stream differs from the stage dtype
     for (int l = 0; l < L; ++l) {
-        const void* x = l == 0 ? io.x : st->ST(slot, l - 1, st->s_y);
+        // block area of the stash: one per block, or two used in turn when nothing is kept
+        const int la = st->keep ? l : (l & 1), lp = st->keep ? l - 1 : ((l - 1) & 1);
+        const void* x = l == 0 ? io.x : st->ST(slot, lp, st->s_y);
         const int x_f32 = wide && l > 0;
-        void* y = l == L - 1 ? io.y : st->ST(slot, l, st->s_y);
+        void* y = l == L - 1 ? io.y : st->ST(slot, la, st->s_y);
         const int y_f32 = wide && l < L - 1;
-        void* h1 = st->ST(slot, l, st->s_h1);
-        void* qkv = st->ST(slot, l, st->s_qkv);
-        void* ctx = st->ST(slot, l, st->s_ctx);
-        void* x1 = st->ST(slot, l, st->s_x1);
-        void* h2 = st->ST(slot, l, st->s_h2);
-        void* u = st->ST(slot, l, st->s_u);
-        void* g = st->ST(slot, l, st->s_g);
-        TRY(st_ln_fwd(st, x, x_f32, st->W(l, st->o_ln1_g), st->W(l, st->o_ln1_b), h1, (float*)st->ST(slot, l, st->s_mean1),
-                      (float*)st->ST(slot, l, st->s_rstd1)));
+        void* h1 = st->ST(slot, la, st->s_h1);
+        void* qkv = st->ST(slot, la, st->s_qkv);
+        void* ctx = st->ST(slot, la, st->s_ctx);
+        void* x1 = st->ST(slot, la, st->s_x1);
+        void* h2 = st->ST(slot, la, st->s_h2);
+        void* u = st->ST(slot, la, st->s_u);
+        void* g = st->ST(slot, la, st->s_g);
+        TRY(st_ln_fwd(st, x, x_f32, st->W(l, st->o_ln1_g), st->W(l, st->o_ln1_b), h1, (float*)st->ST(slot, la, st->s_mean1),
+                      (float*)st->ST(slot, la, st->s_rstd1)));
         TRY(linear_fwd(st, M, 3 * H, H, h1, st->W(l, st->o_w_qkv), st->W(l, st->o_b_qkv), nullptr, qkv, nullptr, EPI_BIAS));
         AttnArgs a{};
         attn_args(st, a);
-        a.qkv = qkv; a.ctx = ctx; a.lse = (float*)st->ST(slot, l, st->s_lse);
+        a.qkv = qkv; a.ctx = ctx; a.lse = (float*)st->ST(slot, la, st->s_lse);
         TRY(st_attn_fwd(st, a));
         TRY(linear_fwd(st, M, H, H, ctx, st->W(l, st->o_w_o), st->W(l, st->o_b_o), x, x1, nullptr, EPI_BIAS_RESIDUAL, x_f32, wide));
-        TRY(st_ln_fwd(st, x1, wide, st->W(l, st->o_ln2_g), st->W(l, st->o_ln2_b), h2, (float*)st->ST(slot, l, st->s_mean2),
-                      (float*)st->ST(slot, l, st->s_rstd2)));
+        TRY(st_ln_fwd(st, x1, wide, st->W(l, st->o_ln2_g), st->W(l, st->o_ln2_b), h2, (float*)st->ST(slot, la, st->s_mean2),
+                      (float*)st->ST(slot, la, st->s_rstd2)));
         TRY(linear_fwd(st, M, 4 * H, H, h2, st->W(l, st->o_w_fc1), st->W(l, st->o_b_fc1), nullptr, u, g, EPI_BIAS_GELU));
         TRY(linear_fwd(st, M, H, 4 * H, g, st->W(l, st->o_w_fc2), st->W(l, st->o_b_fc2), x1, y, nullptr, EPI_BIAS_RESIDUAL, wide, y_f32));
     }
@@ -295,8 +303,16 @@ int stage_forward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
 // The gradient of the residual stream is float as well (dy -> dx1 -> dx); each
 // LayerNorm backward also writes a copy in the stage dtype, which is what the
 // matrix-core products and the bias sums read.
-int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
-    const int M = st->M, H = st->H, L = st->L;
+// Rows [row0, row0 + rows) of the micro-batch (whole sequences): the whole of it, or one
+// half in a half backward (section 3.5, backward halving).  Every operation of a block acts
+// within one sequence, so a part of the rows is an independent backward over the same stash.
+int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot, int row0, int rows) {
+    const int M = rows, H = st->H, L = st->L;
+    st->vM = rows; st->vB = rows / st->S;
+    const size_t e = st->esz, r0 = (size_t)row0;
+    auto shift = [&](const void* p, size_t cols, size_t bytes) { return (const void*)((const char*)p + r0 * cols * bytes); };
+    chimera_stage::IO io = io_full;
+    io.x = shift(io_full.x, H, e); io.dy = shift(io_full.dy, H, e); io.dx = (void*)shift(io_full.dx, H, e);
     const int wide = st->dtype == CHIMERA_BF16;
     float* scratch = (float*)(st->ws + st->w_scratch);
     float* scratch2 = (float*)(st->ws + (st->have_side ? st->w_scratch2 : st->w_scratch));
@@ -316,17 +332,22 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         void* du = st->ws + st->w_du[par];
         void* dx1 = st->ws + st->w_dx1[par];
         void* dqkv = st->ws + st->w_dqkv[par];
-        const void* x = l == 0 ? io.x : st->ST(slot, l - 1, st->s_y);
+        const void* x = l == 0 ? io.x : shift(st->ST(slot, l - 1, st->s_y), H, 4);
         const int x_f32 = wide && l > 0;
         void* dx = l == 0 ? io.dx : (void*)(st->ws + st->w_dy[par]);
         float* dxf = (wide && l > 0) ? (float*)(st->ws + st->w_dyf[par]) : nullptr;
-        const void* h1 = st->ST(slot, l, st->s_h1);
-        const void* qkv = st->ST(slot, l, st->s_qkv);
-        const void* ctx = st->ST(slot, l, st->s_ctx);
-        const void* x1 = st->ST(slot, l, st->s_x1);
-        const void* h2 = st->ST(slot, l, st->s_h2);
-        const void* u = st->ST(slot, l, st->s_u);
-        const void* g = st->ST(slot, l, st->s_g);
+        const void* h1 = shift(st->ST(slot, l, st->s_h1), H, e);
+        const void* qkv = shift(st->ST(slot, l, st->s_qkv), 3 * H, e);
+        const void* ctx = shift(st->ST(slot, l, st->s_ctx), H, e);
+        const void* x1 = shift(st->ST(slot, l, st->s_x1), H, 4);
+        const void* h2 = shift(st->ST(slot, l, st->s_h2), H, e);
+        const void* u = shift(st->ST(slot, l, st->s_u), 4 * H, e);
+        const void* g = shift(st->ST(slot, l, st->s_g), 4 * H, e);
+        const float* mean1 = (const float*)shift(st->ST(slot, l, st->s_mean1), 1, 4);
+        const float* rstd1 = (const float*)shift(st->ST(slot, l, st->s_rstd1), 1, 4);
+        const float* mean2 = (const float*)shift(st->ST(slot, l, st->s_mean2), 1, 4);
+        const float* rstd2 = (const float*)shift(st->ST(slot, l, st->s_rstd2), 1, 4);
+        float* lse = (float*)shift(st->ST(slot, l, st->s_lse), st->heads, 4);       // [sequence, head, position]: heads floats per token
         // With the matrix-core kernels the block's four weight gradients go out as one launch,
         // once the last of their operands (dqkv) exists; otherwise each follows its operands.
         const GemmArgs wg[4] = {wgrad_args(M, H, 4 * H, g, dy, st->G(l, st->o_w_fc2)),
@@ -348,7 +369,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
             TRY(linear_wgrad(st, M, 4 * H, H, h2, du, st->G(l, st->o_w_fc1), gs));
         }
         TRY(linear_dgrad(st, M, 4 * H, H, du, st->W(l, st->o_w_fc1), nullptr, dh, EPI_NONE));
-        TRY(st_ln_bwd(st, dh, x1, wide, (const float*)st->ST(slot, l, st->s_mean2), (const float*)st->ST(slot, l, st->s_rstd2),
+        TRY(st_ln_bwd(st, dh, x1, wide, mean2, rstd2,
                       st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch));
         // x1 = x + ctx Wo + bo
         if (!grouped) {
@@ -359,7 +380,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         TRY(linear_dgrad(st, M, H, H, dx1, st->W(l, st->o_w_o), nullptr, dctx, EPI_NONE));
         AttnArgs a{};
         attn_args(st, a);
-        a.qkv = qkv; a.ctx = (void*)ctx; a.lse = (float*)st->ST(slot, l, st->s_lse);
+        a.qkv = qkv; a.ctx = (void*)ctx; a.lse = lse;
         a.dctx = dctx; a.dqkv = dqkv; a.delta = (float*)(st->ws + st->w_delta);
         TRY(st_attn_bwd(st, a));
         // qkv = h1 Wqkv + bqkv
@@ -376,7 +397,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
         TRY(linear_dgrad(st, M, 3 * H, H, dqkv, st->W(l, st->o_w_qkv), nullptr, dh, EPI_NONE));
         // dx goes into the buffer that the block above read its dy from, also on the side stream
         if (st->have_side && l + 1 <= L - 1) HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_side[(l + 1) & 1], 0));
-        TRY(st_ln_bwd(st, dh, x, x_f32, (const float*)st->ST(slot, l, st->s_mean1), (const float*)st->ST(slot, l, st->s_rstd1),
+        TRY(st_ln_bwd(st, dh, x, x_f32, mean1, rstd1,
                       st->W(l, st->o_ln1_g), wide ? (const void*)dx1f : (const void*)dx1, wide, dx, dxf,
                       st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch));
         dy = dx;
@@ -393,8 +414,8 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io, int slot) {
 }
 
 struct Worker {
-    chimera_stage* down = nullptr;
-    chimera_stage* up = nullptr;
+    std::vector<chimera_stage*> pipes;        // stage of pipeline p (2f of them; 0 = down, 1 = up)
+    chimera_stage* fwd2[2] = {nullptr, nullptr};   // forward-only stages at twice the micro-batch (forward doubling)
     int timing = 0;
     double fwd_ms = 0, bwd_ms = 0;
     int nf = 0, nb = 0;
@@ -433,6 +454,7 @@ int chimera_stage_set_option(chimera_stage* st, int key, int value) {
         case CHIMERA_OPT_GELU: if (value != 0 && value != 1) break; st->gelu_erf = value; return CHIMERA_OK;
         case CHIMERA_OPT_KERNELS: if (value != 0 && value != 1) break; st->kernels = value; return CHIMERA_OK;
         case CHIMERA_OPT_OVERLAP: if (value != 0 && value != 1) break; st->overlap = value; return CHIMERA_OK;
+        case CHIMERA_OPT_KEEP: if (value != 0 && value != 1) break; st->keep = value; layout(st); return CHIMERA_OK;
         default: return fail(CHIMERA_EINVAL, "unknown option %d", key);
     }
     return fail(CHIMERA_EINVAL, "bad value %d for option %d", value, key);
@@ -449,8 +471,8 @@ static void drop_side(chimera_stage* st) {
 
 void chimera_stage_destroy(chimera_stage* st) {
     if (!st) return;
-    if (g_worker.down == st) g_worker.down = nullptr;
-    if (g_worker.up == st) g_worker.up = nullptr;
+    for (chimera_stage*& p : g_worker.pipes) if (p == st) p = nullptr;
+    for (chimera_stage*& p : g_worker.fwd2) if (p == st) p = nullptr;
     drop_side(st);
     delete st;
 }
@@ -504,6 +526,11 @@ int chimera_fwd_slot(chimera_stage* st, int mb, int slot) {
     auto it = st->io.find(mb);
     if (it == st->io.end()) return fail(CHIMERA_ESTATE, "io of micro-batch %d not set", mb);
     if (st->in_flight.count(mb)) return fail(CHIMERA_ESTATE, "forward of micro-batch %d already done", mb);
+    if (!st->keep) {
+        // nothing is kept: the one scratch slot is free again as soon as the kernels are enqueued
+        if (slot > 0) return fail(CHIMERA_ENOMEM, "a forward-only stage has a single scratch slot");
+        return stage_forward(st, it->second, 0);
+    }
     if (slot < 0) {
         slot = 0;
         while (slot < st->slots && st->slot_used[slot]) ++slot;
@@ -527,8 +554,27 @@ int chimera_bwd(chimera_stage* st, int mb) {
     if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
     auto fl = st->in_flight.find(mb);
     if (fl == st->in_flight.end()) return fail(CHIMERA_ESTATE, "backward of micro-batch %d without its forward", mb);
-    int rc = stage_backward(st, st->io[mb], fl->second);
+    if (st->halves_done.count(mb)) return fail(CHIMERA_ESTATE, "micro-batch %d is half-way through a halved backward", mb);
+    int rc = stage_backward(st, st->io[mb], fl->second, 0, st->M);
     if (rc) return rc;
+    st->slot_used[fl->second] = 0;
+    st->in_flight.erase(fl);
+    return CHIMERA_OK;
+}
+
+int chimera_bwd_half(chimera_stage* st, int mb, int half) {
+    if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
+    if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
+    if (half != 0 && half != 1) return fail(CHIMERA_EINVAL, "half=%d must be 0 or 1", half);
+    if (st->B % 2) return fail(CHIMERA_EINVAL, "a micro-batch of %d sequences cannot be halved", st->B);
+    auto fl = st->in_flight.find(mb);
+    if (fl == st->in_flight.end()) return fail(CHIMERA_ESTATE, "backward of micro-batch %d without its forward", mb);
+    const int done = st->halves_done.count(mb) ? st->halves_done[mb] : 0;
+    if (done != half) return fail(CHIMERA_ESTATE, "half %d of micro-batch %d out of order", half, mb);
+    int rc = stage_backward(st, st->io[mb], fl->second, half * (st->M / 2), st->M / 2);
+    if (rc) return rc;
+    if (half == 0) { st->halves_done[mb] = 1; return CHIMERA_OK; }
+    st->halves_done.erase(mb);
     st->slot_used[fl->second] = 0;
     st->in_flight.erase(fl);
     return CHIMERA_OK;
@@ -552,36 +598,82 @@ int chimera_stage_read_grads(chimera_stage* st, float* h_dst, size_t bytes) {
     return CHIMERA_OK;
 }
 
+int chimera_worker_bind_pipes(chimera_stage* const* h_stages, int count) {
+    if (!h_stages || count < 1 || count > 64) return fail(CHIMERA_EINVAL, "1..64 stages expected");
+    for (int i = 0; i < count; ++i) {
+        if (!h_stages[i]) { if (i == 0) return fail(CHIMERA_EINVAL, "stage of pipeline 0 is NULL"); continue; }
+        if (!h_stages[i]->bound) return fail(CHIMERA_ESTATE, "stages must be bound first");
+        if (!h_stages[i]->keep) return fail(CHIMERA_EINVAL, "a forward-only stage cannot serve a pipeline");
+        for (int j = 0; j < i; ++j)
+            if (h_stages[j] == h_stages[i]) return fail(CHIMERA_EINVAL, "the stages of a worker must differ");
+    }
+    g_worker.pipes.assign(h_stages, h_stages + count);
+    g_worker.fwd2[0] = g_worker.fwd2[1] = nullptr;
+    return CHIMERA_OK;
+}
+
 int chimera_worker_bind(chimera_stage* down_stage, chimera_stage* up_stage) {
     if (!down_stage) return fail(CHIMERA_EINVAL, "down stage is NULL");
-    if (!down_stage->bound || (up_stage && !up_stage->bound)) return fail(CHIMERA_ESTATE, "stages must be bound first");
     if (down_stage == up_stage) return fail(CHIMERA_EINVAL, "down and up stage must differ");
-    g_worker.down = down_stage;
-    g_worker.up = up_stage;
+    chimera_stage* both[2] = {down_stage, up_stage};
+    return chimera_worker_bind_pipes(both, 2);
+}
+
+int chimera_worker_bind_doubling(chimera_stage* down2, chimera_stage* up2) {
+    Worker& wk = g_worker;
+    if (wk.pipes.size() != 2 || !wk.pipes[0] || !wk.pipes[1]) return fail(CHIMERA_ESTATE, "bind the worker's two stages first");
+    chimera_stage* two[2] = {down2, up2};
+    for (int p = 0; p < 2; ++p) {
+        const chimera_stage* a = wk.pipes[p];
+        const chimera_stage* b = two[p];
+        if (!b) return fail(CHIMERA_EINVAL, "doubled stage is NULL");
+        if (!b->bound) return fail(CHIMERA_ESTATE, "stages must be bound first");
+        if (b->keep) return fail(CHIMERA_EINVAL, "the doubled stage must be forward-only (CHIMERA_OPT_KEEP = 0)");
+        if (b->L != a->L || b->H != a->H || b->heads != a->heads || b->S != a->S || b->dtype != a->dtype || b->B != 2 * a->B ||
+            b->causal != a->causal || b->gelu_erf != a->gelu_erf)
+            return fail(CHIMERA_EINVAL, "the doubled stage must have the pipeline stage's shape at twice the micro-batch");
+        if (b->weights != a->weights) return fail(CHIMERA_EINVAL, "the doubled stage must be bound to the same weights");
+    }
+    wk.fwd2[0] = down2; wk.fwd2[1] = up2;
     return CHIMERA_OK;
 }
 
 int chimera_worker_set_timing(int on) { g_worker.timing = on ? 1 : 0; return CHIMERA_OK; }
 
-int chimera_run_worker_algo(int algo, int rank, int D, int N) {
+int chimera_run_worker_pipes(int algo, int rank, int D, int N, int f) {
     Worker& wk = g_worker;
-    if (!wk.down) return fail(CHIMERA_ESTATE, "no worker bound");
+    if (wk.pipes.empty() || !wk.pipes[0]) return fail(CHIMERA_ESTATE, "no worker bound");
     std::vector<std::vector<Op>> lists;
-    TRY(build_schedule(algo, D, N, lists));
+    TRY(build_schedule(algo, D, N, f, lists));
     if (rank < 0 || rank >= D) return fail(CHIMERA_EINVAL, "rank %d outside [0,%d)", rank, D);
     TRY(annotate(lists, D, N));
     const std::vector<Op>& ops = lists[rank];
-    chimera_stage* stage_of[2] = {wk.down, wk.up};
-    int need[2] = {0, 0};
-    for (const Op& o : ops) need[o.pipe] = std::max(need[o.pipe], o.slot + 1);
-    for (int p = 0; p < 2; ++p) {
-        if (!need[p]) continue;
-        chimera_stage* st = stage_of[p];
-        if (!st) return fail(CHIMERA_ESTATE, "schedule uses the up pipeline but no up stage is bound");
-        if (st->slots < need[p]) return fail(CHIMERA_ENOMEM, "%s stage bound with %d stash slots, schedule needs %d", p ? "up" : "down", st->slots, need[p]);
-        if (!st->in_flight.empty()) return fail(CHIMERA_ESTATE, "%s stage has micro-batches in flight", p ? "up" : "down");
-        for (const Op& o : ops)
-            if (o.pipe == p && !st->io.count(o.mb)) return fail(CHIMERA_ESTATE, "io of micro-batch %d not set on the %s stage", o.mb, p ? "up" : "down");
+    const int pipes = (int)wk.pipes.size();
+    std::vector<int> need(pipes, 0);
+    bool recompute = false;
+    for (const Op& o : ops) {
+        if (o.pipe >= pipes || !wk.pipes[o.pipe]) return fail(CHIMERA_ESTATE, "schedule uses pipeline %d but no stage is bound for it", o.pipe);
+        need[o.pipe] = std::max(need[o.pipe], o.slot + 1);
+        if (o.kind == CHIMERA_OP_F2) recompute = true;
+    }
+    for (int p = 0; p < pipes; ++p) {
+        chimera_stage* st = wk.pipes[p];
+        if (!st || (!need[p] && !recompute)) continue;
+        // a backward after a doubled forward recomputes into one more slot
+        const int slots = need[p] + (recompute ? 1 : 0);
+        if (st->slots < slots) return fail(CHIMERA_ENOMEM, "stage of pipeline %d bound with %d stash slots, schedule needs %d", p, st->slots, slots);
+        if (!st->in_flight.empty()) return fail(CHIMERA_ESTATE, "stage of pipeline %d has micro-batches in flight", p);
+    }
+    for (const Op& o : ops) {
+        chimera_stage* st = wk.pipes[o.pipe];
+        if (o.kind == CHIMERA_OP_F2) {
+            if (o.pipe > 1 || !wk.fwd2[o.pipe]) return fail(CHIMERA_ESTATE, "forward doubling needs chimera_worker_bind_doubling");
+            if (!wk.fwd2[o.pipe]->io.count(o.mb)) return fail(CHIMERA_ESTATE, "io of micro-batches %d,%d not set on the doubled stage", o.mb, o.mb + 1);
+        } else if (!st->io.count(o.mb)) {
+            return fail(CHIMERA_ESTATE, "io of micro-batch %d not set on the stage of pipeline %d", o.mb, o.pipe);
+        }
+        if ((o.kind == CHIMERA_OP_BH0 || o.kind == CHIMERA_OP_BH1) && (st->B % 2))
+            return fail(CHIMERA_EINVAL, "a micro-batch of %d sequences cannot be halved", st->B);
     }
     std::vector<hipEvent_t> ev;
     if (wk.timing) {
@@ -592,19 +684,39 @@ int chimera_run_worker_algo(int algo, int rank, int D, int N) {
     int rc = CHIMERA_OK;
     for (size_t i = 0; i < ops.size() && !rc; ++i) {
         const Op& o = ops[i];
-        chimera_stage* st = stage_of[o.pipe];
+        chimera_stage* st = wk.pipes[o.pipe];
         if (wk.timing) (void)hipEventRecord(ev[2 * i], st->stream);
-        rc = o.kind == 0 ? chimera_fwd_slot(st, o.mb, o.slot) : chimera_bwd(st, o.mb);
+        switch (o.kind) {
+            case CHIMERA_OP_F: rc = chimera_fwd_slot(st, o.mb, o.slot); break;
+            case CHIMERA_OP_F2: rc = chimera_fwd_slot(wk.fwd2[o.pipe], o.mb, 0); break;
+            case CHIMERA_OP_B:
+                // after a doubled forward nothing was kept: run the forward again, then the backward
+                if (!st->in_flight.count(o.mb)) rc = chimera_fwd_slot(st, o.mb, -1);
+                if (!rc) rc = chimera_bwd(st, o.mb);
+                break;
+            case CHIMERA_OP_BH0: rc = chimera_bwd_half(st, o.mb, 0); break;
+            case CHIMERA_OP_BH1: rc = chimera_bwd_half(st, o.mb, 1); break;
+            default: rc = fail(CHIMERA_EINVAL, "unknown op kind %d", o.kind);
+        }
         if (wk.timing) (void)hipEventRecord(ev[2 * i + 1], st->stream);
     }
-    hipError_t e = hipStreamSynchronize(wk.down->stream);
-    if (e == hipSuccess && wk.up && wk.up->stream != wk.down->stream) e = hipStreamSynchronize(wk.up->stream);
+    // one wait per distinct stream
+    hipError_t e = hipSuccess;
+    std::vector<hipStream_t> waited;
+    auto wait = [&](chimera_stage* st) {
+        if (!st || e != hipSuccess) return;
+        for (hipStream_t s : waited) if (s == st->stream) return;
+        waited.push_back(st->stream);
+        e = hipStreamSynchronize(st->stream);
+    };
+    for (chimera_stage* st : wk.pipes) wait(st);
+    for (chimera_stage* st : wk.fwd2) wait(st);
     if (wk.timing) {
         wk.fwd_ms = wk.bwd_ms = 0; wk.nf = wk.nb = 0;
         for (size_t i = 0; i < ops.size(); ++i) {
             float ms = 0.f;
             if (!rc && e == hipSuccess && hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) == hipSuccess) {
-                if (ops[i].kind == 0) { wk.fwd_ms += ms; ++wk.nf; } else { wk.bwd_ms += ms; ++wk.nb; }
+                if (ops[i].kind == CHIMERA_OP_F || ops[i].kind == CHIMERA_OP_F2) { wk.fwd_ms += ms; ++wk.nf; } else { wk.bwd_ms += ms; ++wk.nb; }
             }
             (void)hipEventDestroy(ev[2 * i]);
             (void)hipEventDestroy(ev[2 * i + 1]);
@@ -615,7 +727,9 @@ int chimera_run_worker_algo(int algo, int rank, int D, int N) {
     return CHIMERA_OK;
 }
 
-int chimera_run_worker(int rank, int D, int N) { return chimera_run_worker_algo(CHIMERA_DIRECT, rank, D, N); }
+int chimera_run_worker_algo(int algo, int rank, int D, int N) { return chimera_run_worker_pipes(algo, rank, D, N, 1); }
+
+int chimera_run_worker(int rank, int D, int N) { return chimera_run_worker_pipes(CHIMERA_DIRECT, rank, D, N, 1); }
 
 int chimera_worker_last_timing(double* h_fwd_ms, double* h_bwd_ms, int* h_nf, int* h_nb) {
     if (h_fwd_ms) *h_fwd_ms = g_worker.fwd_ms;

@@ -268,3 +268,67 @@ def test_bf16_rounding_helper():
     want = torch.tensor(a).to(torch.bfloat16).to(torch.float32).numpy()
     np.testing.assert_array_equal(r, want)
     assert r[1] == 1.0 and r[3] == np.float32(1.0 + 2 ** -6)   # ties go to even
+
+
+# ------------------------------------------------------------ op-by-op replay (sections 3.5, 3.6)
+def _replay_case(D, N, f, batch):
+    from oracle import schedule_oracle as so
+    hidden, heads, seq, layers = 16, 2, 4, 1
+    rng = np.random.default_rng(5)
+    xs = {g: rng.standard_normal((batch * seq, hidden)) for g in range(N)}
+    dys = {g: rng.standard_normal((batch * seq, hidden)) for g in range(N)}
+    stage_params = {s: _params(hidden, layers, seed=10 + s) for s in range(D)}
+    return so, xs, dys, stage_params, (batch, seq, heads)
+
+
+def _sum_by_stage(D, N, xs, dys, stage_params, shape, stage_of_mb):
+    """Per-stage gradient sums and per-micro-batch outputs from the plain stage pass."""
+    batch, seq, heads = shape
+    ys, dxs, grads = {}, {}, {}
+    for g in range(N):
+        s = stage_of_mb(g)
+        y, dx, gr = bo.stage_pass(xs[g], dys[g], stage_params[s], batch, seq, heads)
+        ys[g], dxs[g] = y, dx
+        grads[s] = bo.add_grads(grads.get(s), gr)
+    return ys, dxs, grads
+
+
+@pytest.mark.parametrize("mode", ["direct", "doubling", "halving", "2f"])
+def test_worker_replay_is_order_independent(mode):
+    """Whatever the schedule, a synchronous iteration gives every micro-batch's stage pass and
+    the per-stage sum of gradients (section 2: one weight version per iteration)."""
+    D, f, batch = (8, 2, 2) if mode == "2f" else (4, 1, 2)
+    N = 2 * D if mode == "doubling" else D
+    rank = 1
+    so, xs, dys, stage_params, shape = _replay_case(D, N, f, batch)
+    lists = {"direct": lambda: so.chimera_schedule(D, N), "doubling": lambda: so.forward_doubling_schedule(D, N),
+             "halving": lambda: so.backward_halving_schedule(D, N), "2f": lambda: so.chimera_schedule(D, N, f)}[mode]()
+    ops = lists[rank]
+    stage_of_pipe = {pipe: s for _, pipe, _, s in ops}
+    pipe_of_mb = {}
+    for kind, pipe, g, s in ops:
+        pipe_of_mb[g] = pipe
+        if kind == so.F2:
+            pipe_of_mb[g + 1] = pipe
+    ys, dxs, grads = bo.worker_replay(ops, {p: stage_params[s] for p, s in stage_of_pipe.items()}, xs, dys, *shape)
+    want_y, want_dx, want_g = _sum_by_stage(D, N, xs, dys, stage_params, shape, lambda g: stage_of_pipe[pipe_of_mb[g]])
+    assert sorted(ys) == sorted(dxs) == list(range(N))
+    for g in range(N):
+        np.testing.assert_allclose(ys[g], want_y[g], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(dxs[g], want_dx[g], rtol=1e-10, atol=1e-12)
+    for pipe, s in stage_of_pipe.items():
+        for got_layer, want_layer in zip(grads[pipe], want_g[s]):
+            for k in want_layer:
+                np.testing.assert_allclose(got_layer[k], want_layer[k], rtol=1e-9, atol=1e-11)
+
+
+def test_doubled_forward_equals_two_forwards():
+    # sequences never mix inside a block: a forward over the concatenation is the two forwards
+    hidden, heads, seq, batch = 16, 2, 5, 3
+    rng = np.random.default_rng(8)
+    p = bo._f64(_params(hidden, 2, seed=3))
+    xa, xb = rng.standard_normal((batch * seq, hidden)), rng.standard_normal((batch * seq, hidden))
+    y2, _ = bo.stage_fwd(np.concatenate([xa, xb]), p, 2 * batch, seq, heads)
+    ya, _ = bo.stage_fwd(xa, p, batch, seq, heads)
+    yb, _ = bo.stage_fwd(xb, p, batch, seq, heads)
+    np.testing.assert_allclose(y2, np.concatenate([ya, yb]), rtol=1e-13, atol=1e-13)
