@@ -60,6 +60,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="single stream per stage (analysis only)")
+    ap.add_argument("--schedule", choices=["direct", "doubling", "halving"], default="direct",
+                    help="direct concatenation (the headline workload), forward doubling with recomputation, or backward halving")
+    ap.add_argument("--micro-batches", type=int, default=0, help="N (default: the workload's; doubling needs >= 2D)")
+    ap.add_argument("--f", type=int, default=1, help="2f pipelines per worker (direct schedule only)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs one Chimera worker on ONE GPU; --gpus %d is not supported "
@@ -72,25 +76,47 @@ def main():
 
     cfg = synth.CONFIGS[args.config]
     dtype = b.F32 if cfg.dtype == "f32" else b.BF16
-    D, N, rank = cfg.D, cfg.N, args.rank
-    need = b.stash_slots_needed(b.DIRECT, D, N, rank)
-    stages = []
-    for pipe, stage_id in ((0, rank), (1, D - 1 - rank)):
-        st = b.Stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, dtype, causal=cfg.causal,
-                     stash_slots=need[pipe], overlap=not args.no_overlap)
-        st.set_weights(synth.flatten_params(synth.make_stage_params(cfg.hidden, cfg.layers, stage_id, 0, cfg.dtype)))
-        stages.append(st)
+    D, rank, f = cfg.D, args.rank, args.f
+    algo = {"direct": b.DIRECT, "doubling": b.DOUBLING, "halving": b.HALVING}[args.schedule]
+    N = args.micro_batches or (2 * cfg.N if algo == b.DOUBLING and cfg.N < 2 * D else cfg.N)
+    ops = b.chimera_schedule_pipes(algo, D, N, f, rank)
+    need = b.stash_slots_needed_pipes(algo, D, N, f, rank)
+    stage_of_pipe = {o.pipe: o.stage for o in ops}
     tdt = torch.float32 if dtype == b.F32 else torch.bfloat16
-    for g in range(N):
-        x, dy = synth.make_microbatch(cfg.tokens, cfg.hidden, g, 0, cfg.dtype)
-        pipe = 0 if (g % D) < D // 2 else 1
-        stages[pipe].set_io(g, torch.from_numpy(x).cuda().to(tdt), torch.from_numpy(dy).cuda().to(tdt))
-    b.chimera_worker_bind(stages[0], stages[1])
+    stages = {}
+    for pipe, stage_id in sorted(stage_of_pipe.items()):
+        st = b.Stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, dtype, causal=cfg.causal,
+                     stash_slots=max(need[pipe], 1), overlap=not args.no_overlap)
+        st.set_weights(synth.flatten_params(synth.make_stage_params(cfg.hidden, cfg.layers, stage_id, 0, cfg.dtype)))
+        stages[pipe] = st
+    doubled = {}
+    if algo == b.DOUBLING:
+        for pipe in (0, 1):
+            doubled[pipe] = b.Stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, 2 * cfg.microbatch, dtype, causal=cfg.causal,
+                                    keep=False, share_weights_of=stages[pipe], overlap=not args.no_overlap)
+    dev = lambda a: torch.from_numpy(a).cuda().to(tdt)
+    done = set()
+    for o in ops:
+        if o.kind == b.OP_F2:               # the pair's inputs side by side; each micro-batch's io aliases its half
+            pair = [synth.make_microbatch(cfg.tokens, cfg.hidden, o.mb + j, 0, cfg.dtype) for j in (0, 1)]
+            x2 = dev(np.concatenate([pair[0][0], pair[1][0]]))
+            doubled[o.pipe].set_io(o.mb, x2, x2)
+            for j in (0, 1):
+                stages[o.pipe].set_io(o.mb + j, x2[j * cfg.tokens:(j + 1) * cfg.tokens], dev(pair[j][1]))
+                done.add(o.mb + j)
+    for o in ops:
+        if o.mb not in done:
+            x, dy = synth.make_microbatch(cfg.tokens, cfg.hidden, o.mb, 0, cfg.dtype)
+            stages[o.pipe].set_io(o.mb, dev(x), dev(dy))
+            done.add(o.mb)
+    b.chimera_worker_bind_pipes([stages.get(p) for p in range(2 * f)])
+    if doubled:
+        b.chimera_worker_bind_doubling(doubled[0], doubled[1])
 
     def step():
-        stages[0].zero_grads()
-        stages[1].zero_grads()
-        b.chimera_run_worker(rank, D, N)
+        for st in stages.values():
+            st.zero_grads()
+        b.chimera_run_worker_pipes(algo, rank, D, N, f)
 
     for _ in range(args.warmup):
         step()
@@ -109,10 +135,12 @@ def main():
         "value": seq_per_s, "unit": "sequences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "host_enqueue_ms_per_step": enqueue * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "D": D, "N": N, "rank": rank, "blocks_per_stage": cfg.layers,
-                   "hidden": cfg.hidden, "heads": cfg.heads, "seq": cfg.seq, "microbatch": cfg.microbatch,
-                   "causal": cfg.causal, "stash_slots": {"down": need[0], "up": need[1]},
-                   "stash_bytes": int(stages[0].slot_bytes * need[0] + stages[1].slot_bytes * need[1])},
+        "config": {"workload": cfg.name, "schedule": args.schedule, "pipelines_per_worker": 2 * f, "D": D, "N": N, "rank": rank,
+                   "blocks_per_stage": cfg.layers, "hidden": cfg.hidden, "heads": cfg.heads, "seq": cfg.seq,
+                   "microbatch": cfg.microbatch, "causal": cfg.causal,
+                   "stash_slots": {("down" if p % 2 == 0 else "up") + (str(p // 2) if f > 1 else ""): need[p] for p in sorted(stages)},
+                   "stash_bytes": int(sum(st.slot_bytes * st.stash_slots for st in stages.values())
+                                      + sum(st.slot_bytes for st in doubled.values()))},
     }
 
     if not args.no_profile:
@@ -162,12 +190,27 @@ def main():
         f_us = max(1, int(round(out["stage_times"]["F_t_ms"] * 1e3)))
         b_us = max(1, int(round(out["stage_times"]["B_t_ms"] * 1e3)))
         proj = {}
-        for name, algo in (("chimera", b.DIRECT), ("1f1b", b.ONE_F_ONE_B), ("gpipe", b.GPIPE)):
-            st = b.chimera_schedule_stats(algo, D, N, f_us, b_us)
+        for name, alg in (("chimera", b.DIRECT), ("1f1b", b.ONE_F_ONE_B), ("gpipe", b.GPIPE)):
+            st = b.chimera_schedule_stats(alg, D, N, f_us, b_us)
             proj[name] = {"makespan_ms": st["makespan"] / 1e3,
                           "sequences_per_s_per_pipeline": N * cfg.microbatch / (st["makespan"] * 1e-6),
                           "bubble_frac": st["bubbles"][rank] / st["makespan"], "stash_peak": max(st["stash_peak"])}
         out["pipeline_projection"] = proj
+        # Eq. (1) of the paper's performance model with the measured stage times and an assumed link:
+        # one xGMI link per neighbour pair (153 GB/s, 5 us latency); words are bytes here
+        if algo == b.DIRECT:
+            esz = 4 if dtype == b.F32 else 2
+            alpha, beta = 5e-6, 1.0 / 153e9
+            act = float(cfg.microbatch * cfg.seq * cfg.hidden * esz)
+            grad = float(stages[0].grads.numel() * 4)
+            model = {}
+            for name, alg, ff in (("chimera", b.DIRECT, f), ("1f1b", b.ONE_F_ONE_B, 1), ("gpipe", b.GPIPE, 1)):
+                m = b.chimera_model_iteration_time(alg, D, N, ff, 1, out["stage_times"]["F_t_ms"] * 1e-3,
+                                                   out["stage_times"]["B_t_ms"] * 1e-3, alpha, beta, act, grad)
+                model[name] = {"T_ms": m["T"] * 1e3, "C_f": m["c_f"], "C_b": m["c_b"], "p2p_ms": m["p2p"] * 1e3,
+                               "allreduce_ms": m["allreduce"] * 1e3, "unoverlapped_ms": m["unoverlapped"] * 1e3,
+                               "sequences_per_s_per_pipeline": N * cfg.microbatch / m["T"]}
+            out["model_eq1"] = {"assumed": {"alpha_s": alpha, "beta_s_per_byte": beta, "W": 1}, **model}
 
     if dtype == b.BF16:
         # what this chip sustains: register-resident MFMA loop on every SIMD, and a streaming copy
