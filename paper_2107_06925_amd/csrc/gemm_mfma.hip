@@ -716,10 +716,10 @@ int launch_async(const GemmArgs& g, hipStream_t s) {
     return CHIMERA_OK;
 }
 
-template <int WGK, int NS>
+template <int BM, int BN, int WGM, int WGN, int WGK, int NS>
 int launch_group(const GemmGroup& grp, hipStream_t s) {
-    const dim3 grid(grp.first[grp.count]), block(2 * 2 * WGK * 64);
-    hipLaunchKernelGGL((gemm_bf16_async_group_kernel<128, 128, 2, 2, WGK, NS, false, false>), grid, block, 0, s, grp);
+    const dim3 grid(grp.first[grp.count]), block(WGM * WGN * WGK * 64);
+    hipLaunchKernelGGL((gemm_bf16_async_group_kernel<BM, BN, WGM, WGN, WGK, NS, false, false>), grid, block, 0, s, grp);
     CHIMERA_LAUNCH_CHECK("bf16 gemm group");
     return CHIMERA_OK;
 }
@@ -792,6 +792,12 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, void*
     if (!gemm_mfma_group_supports(count, g))
         return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
                     "one contraction length (a multiple of %d)", GROUP_MAX, BK);
+    // tile choice as for single products: 256x256 once such tiles fill the chip, else 128x128
+    long t256 = 0;
+    for (int i = 0; i < count; ++i) t256 += (long)((g[i].m + 255) / 256) * ((g[i].n + 255) / 256);
+    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");
+    const TileChoice forced = forced_tile();
+    const int tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= NUM_CUS ? 256 : 128);
     GemmGroup grp{};
     grp.count = count; grp.k = g[0].k;
     int tiles = 0;
@@ -799,16 +805,16 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, void*
         grp.a[i] = (const bf16_t*)g[i].a; grp.b[i] = (const bf16_t*)g[i].b; grp.c[i] = (float*)g[i].c;
         grp.bsum[i] = bsum ? bsum[i] : nullptr;
         grp.m[i] = g[i].m; grp.n[i] = g[i].n; grp.lda[i] = g[i].lda; grp.ldb[i] = g[i].ldb;
-        grp.tiles_m[i] = (g[i].m + 127) / 128; grp.tiles_n[i] = (g[i].n + 127) / 128;
+        grp.tiles_m[i] = (g[i].m + tile - 1) / tile; grp.tiles_n[i] = (g[i].n + tile - 1) / tile;
         grp.first[i] = tiles;
         tiles += grp.tiles_m[i] * grp.tiles_n[i];
     }
     for (int i = count; i <= GROUP_MAX; ++i) grp.first[i] = tiles;
-    // same choice as for a single product: two workgroups per CU or the k-sliced 8-wavefront form
-    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");
+    if (tile == 256) return launch_group<256, 256, 2, 4, 1, 2>(grp, (hipStream_t)stream);
+    // two workgroups per CU or the k-sliced 8-wavefront form
     const bool ksplit = mode ? !std::strcmp(mode, "4k") : tiles < 2 * NUM_CUS;
-    if (ksplit) return launch_group<2, 3>(grp, (hipStream_t)stream);
-    return launch_group<1, 2>(grp, (hipStream_t)stream);
+    if (ksplit) return launch_group<128, 128, 2, 2, 2, 3>(grp, (hipStream_t)stream);
+    return launch_group<128, 128, 2, 2, 1, 2>(grp, (hipStream_t)stream);
 }
 
 }  // namespace chimera

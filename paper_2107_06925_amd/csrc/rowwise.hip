@@ -158,6 +158,89 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
     for (int i = threadIdx.x; i < 2 * cols; i += LN_WAVES * WAVE) out[i] = red[i];
 }
 
+// Wide rows (more than two 16-byte chunks per lane of one wavefront): the whole workgroup
+// shares a row, so a thread keeps one chunk (MAXT of them beyond 256 chunks) instead of
+// four or eight, and the column sums of its chunks never leave its registers.  The row's
+// two sums meet in LDS, double-buffered by row parity (one barrier per row).
+constexpr int LNW_THREADS = 256;
+template <typename TX, typename TR, typename T, int MAXT>
+__global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __restrict__ dy, const TX* __restrict__ x,
+                                                                  const float* __restrict__ mean,
+                                                                  const float* __restrict__ rstd,
+                                                                  const T* __restrict__ gamma, const TR* __restrict__ res,
+                                                                  T* __restrict__ dx_lo, float* __restrict__ dx_hi,
+                                                                  float* __restrict__ partial, int rows, int cols) {
+    constexpr int V = Elem<T>::VEC;
+    constexpr int NW = LNW_THREADS / WAVE;
+    __shared__ float sums[2][NW][2];
+    const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE;
+    const int nchunk = cols / V;
+    float ag[MAXT][V], ab[MAXT][V], g[MAXT][V];
+#pragma unroll
+    for (int t = 0; t < MAXT; ++t) {
+        const int c = tid + t * LNW_THREADS;
+#pragma unroll
+        for (int e = 0; e < V; ++e) { ag[t][e] = 0.f; ab[t][e] = 0.f; g[t][e] = 0.f; }
+        if (c < nchunk) load_vec<T>(gamma + c * V, g[t]);
+    }
+    const int row0 = blockIdx.x * LNB_ROWS;
+    const int nrow = min(LNB_ROWS, rows - row0);              // the same for every thread of the block
+    for (int rr = 0; rr < nrow; ++rr) {
+        const int row = row0 + rr;
+        const float mu = mean[row], rs = rstd[row];
+        float dxh[MAXT][V], xh[MAXT][V];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) {
+            const int c = tid + t * LNW_THREADS;
+            if (c < nchunk) {
+                float d[V], xv[V];
+                load_vec<T>(dy + (size_t)row * cols + c * V, d);
+                load_elems<TX, V>(x + (size_t)row * cols + c * V, xv);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    xh[t][e] = (xv[e] - mu) * rs;
+                    dxh[t][e] = d[e] * g[t][e];
+                    s1 += dxh[t][e];
+                    s2 += dxh[t][e] * xh[t][e];
+                    ag[t][e] += d[e] * xh[t][e];
+                    ab[t][e] += d[e];
+                }
+            }
+        }
+        s1 = wave_sum(s1);
+        s2 = wave_sum(s2);
+        if (lane == 0) { sums[rr & 1][wave][0] = s1; sums[rr & 1][wave][1] = s2; }
+        __syncthreads();
+        float m1 = 0.f, m2 = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) { m1 += sums[rr & 1][w][0]; m2 += sums[rr & 1][w][1]; }
+        m1 /= (float)cols;
+        m2 /= (float)cols;
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) {
+            const int c = tid + t * LNW_THREADS;
+            if (c < nchunk) {
+                float rv[V], o[V];
+                load_elems<TR, V>(res + (size_t)row * cols + c * V, rv);
+#pragma unroll
+                for (int e = 0; e < V; ++e) o[e] = rv[e] + rs * (dxh[t][e] - m1 - xh[t][e] * m2);
+                if (dx_lo) store_vec<T>(dx_lo + (size_t)row * cols + c * V, o);
+                if (dx_hi) store_elems<float, V>(dx_hi + (size_t)row * cols + c * V, o);
+            }
+        }
+    }
+    float* out = partial + (size_t)blockIdx.x * 2 * cols;
+#pragma unroll
+    for (int t = 0; t < MAXT; ++t) {
+        const int c = tid + t * LNW_THREADS;
+        if (c < nchunk) {
+            store_elems<float, V>(out + c * V, ag[t]);
+            store_elems<float, V>(out + cols + c * V, ab[t]);
+        }
+    }
+}
+
 // ---------------------------------------------------------------- column sum
 // partial[blockIdx.y][cols] = sum of CS_ROWS rows of x; lanes own columns.
 template <typename T>
@@ -265,12 +348,17 @@ int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float
 #define LN_BWD_CASE(N)                                                                                              \
     hipLaunchKernelGGL((ln_bwd_kernel<TX, TR, T, N>), grid, block, lds, s, (const T*)dy, (const TX*)x, mean, rstd,   \
                        (const T*)gamma, (const TR*)res, (T*)dx_lo, dx_hi, scratch, rows, cols)
+#define LN_BWD_WIDE(N)                                                                                              \
+    hipLaunchKernelGGL((ln_bwd_wide_kernel<TX, TR, T, N>), grid, dim3(LNW_THREADS), 0, s, (const T*)dy, (const TX*)x,   \
+                       mean, rstd, (const T*)gamma, (const TR*)res, (T*)dx_lo, dx_hi, scratch, rows, cols)
+    const int per_thread = (cols / V + LNW_THREADS - 1) / LNW_THREADS;
     if (per_lane <= 1) LN_BWD_CASE(1);
     else if (per_lane <= 2) LN_BWD_CASE(2);
-    else if (per_lane <= 4) LN_BWD_CASE(4);
-    else if (per_lane <= 8) LN_BWD_CASE(8);
-    else return fail(CHIMERA_EINVAL, "LayerNorm width %d too large for the backward (max %d)", cols, 8 * WAVE * V);
+    else if (per_thread <= 1) LN_BWD_WIDE(1);
+    else if (per_thread <= 2) LN_BWD_WIDE(2);
+    else return fail(CHIMERA_EINVAL, "LayerNorm width %d too large for the backward (max %d)", cols, 2 * LNW_THREADS * V);
 #undef LN_BWD_CASE
+#undef LN_BWD_WIDE
     CHIMERA_LAUNCH_CHECK("layernorm backward");
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * cols + 31) / 32), dim3(256), 0, s, scratch, nblk, 2 * cols,
                        dgamma, dbeta, cols);
