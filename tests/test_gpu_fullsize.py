@@ -16,6 +16,18 @@ from gpu_util import assert_close, compare_grads, make_stage, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
+_ORACLE = {}
+
+
+def _oracle_pass(cfg, params, stage_id, g, x, dy):
+    """Oracle stage pass of one micro-batch, computed once per (stage, micro-batch) and session
+    (the weights depend on the stage id only, the inputs on the micro-batch id only)."""
+    key = (cfg.name, stage_id, g)
+    if key not in _ORACLE:
+        print("oracle: stage %d, micro-batch %d" % (stage_id, g), flush=True)
+        _ORACLE[key] = bo.stage_pass(x, dy, params, cfg.microbatch, cfg.seq, cfg.heads, cfg.causal)
+    return _ORACLE[key]
+
 
 def test_bert48_worker_full_size():
     """BERT-48-like worker exactly as benchmarked: D=4, N=4, rank 0, 12 blocks per stage,
@@ -46,8 +58,7 @@ def test_bert48_worker_full_size():
     b.chimera_run_worker(rank, D, N)
     torch.cuda.synchronize()
     for pipe, g in sampled.items():
-        print("oracle: stage pass of micro-batch", g, flush=True)
-        y, dx, gr = bo.stage_pass(xs[g], dys[g], params[pipe], cfg.microbatch, cfg.seq, cfg.heads, cfg.causal)
+        y, dx, gr = _oracle_pass(cfg, params[pipe], (rank, D - 1 - rank)[pipe], g, xs[g], dys[g])
         ey = assert_close(to_np(outs[g][0]), y, b.BF16, "y of micro-batch %d" % g)
         ex = assert_close(to_np(outs[g][1]), dx, b.BF16, "dx of micro-batch %d" % g)
         print("micro-batch %d: y rel err %.3e, dx rel err %.3e" % (g, ey, ex), flush=True)
@@ -56,6 +67,64 @@ def test_bert48_worker_full_size():
     # micro-batches with dY = 0 give dX = 0 exactly
     assert float(outs[1][1].float().abs().max()) == 0.0
     for st in stages:
+        st.close()
+
+
+@pytest.mark.parametrize("schedule", ["halving", "doubling"])
+def test_bert48_worker_full_size_generalised(schedule):
+    """The same worker under backward halving (N=4) and forward doubling with recomputation
+    (N=8), as `bench.py --schedule ...` runs them: the doubled forward works on 8192 rows, the
+    half backward on 2048.  Same dY = 0 device as above."""
+    import torch
+    cfg = synth.CONFIGS["bert48-bf16"]
+    rank, D = 0, cfg.D
+    algo, N = (b.HALVING, 4) if schedule == "halving" else (b.DOUBLING, 8)
+    ops = b.chimera_schedule_pipes(algo, D, N, 1, rank)
+    need = b.stash_slots_needed_pipes(algo, D, N, 1, rank)
+    stages, params, doubled = {}, {}, {}
+    for pipe, sid in ((0, rank), (1, D - 1 - rank)):
+        stages[pipe], params[pipe] = make_stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, b.BF16, sid,
+                                                causal=cfg.causal, stash_slots=max(need[pipe], 1))
+        if algo == b.DOUBLING:
+            doubled[pipe] = b.Stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, 2 * cfg.microbatch, b.BF16, causal=cfg.causal,
+                                    keep=False, share_weights_of=stages[pipe])
+    pipe_of = {}
+    for o in ops:
+        for g in ((o.mb, o.mb + 1) if o.kind == b.OP_F2 else (o.mb,)):
+            pipe_of[g] = o.pipe
+    # one micro-batch per stage keeps its dY; for doubling one is the first, one the second of a pair
+    sampled = {0: 0, 1: 3} if algo == b.HALVING else {0: 0, 1: max(g for g, p in pipe_of.items() if p == 1)}
+    xs, dys, outs = {}, {}, {}
+    for g in range(N):
+        x, dy = synth.make_microbatch(cfg.tokens, cfg.hidden, g, 0, "bf16")
+        xs[g], dys[g] = x, (dy if sampled[pipe_of[g]] == g else np.zeros_like(dy))
+    for o in ops:
+        if o.kind == b.OP_F2:
+            x2 = to_dev(np.concatenate([xs[o.mb], xs[o.mb + 1]]), b.BF16)
+            doubled[o.pipe].set_io(o.mb, x2, x2)
+            for j in (0, 1):
+                outs[o.mb + j] = stages[o.pipe].set_io(o.mb + j, x2[j * cfg.tokens:(j + 1) * cfg.tokens],
+                                                       to_dev(dys[o.mb + j], b.BF16))
+    for g in range(N):
+        if g not in outs:
+            outs[g] = stages[pipe_of[g]].set_io(g, to_dev(xs[g], b.BF16), to_dev(dys[g], b.BF16))
+    b.chimera_worker_bind_pipes([stages[0], stages[1]])
+    if doubled:
+        b.chimera_worker_bind_doubling(doubled[0], doubled[1])
+    b.chimera_run_worker_pipes(algo, rank, D, N, 1)
+    torch.cuda.synchronize()
+    for pipe, g in sampled.items():
+        y, dx, gr = _oracle_pass(cfg, params[pipe], (rank, D - 1 - rank)[pipe], g, xs[g], dys[g])
+        ey = assert_close(to_np(outs[g][0]), y, b.BF16, "y of micro-batch %d" % g)
+        ex = assert_close(to_np(outs[g][1]), dx, b.BF16, "dx of micro-batch %d" % g)
+        eg = compare_grads(stages[pipe].read_grads(), gr, cfg.layers, cfg.hidden, b.BF16, "stage of pipe %d" % pipe)
+        print("%s micro-batch %d: y %.3e, dx %.3e, worst gradient %.3e" % (schedule, g, ey, ex, eg), flush=True)
+        if algo == b.DOUBLING:
+            # the doubled forward (8192 rows, other tile shapes) wrote the same y as the recomputing forward re-wrote
+            pair = g - g % 2
+            y2 = doubled[pipe].io[pair][1][(g - pair) * cfg.tokens:(g - pair + 1) * cfg.tokens]
+            assert_close(to_np(y2), y, b.BF16, "doubled forward's y of micro-batch %d" % g)
+    for st in list(stages.values()) + list(doubled.values()):
         st.close()
 
 
