@@ -173,20 +173,75 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, WAVE); }
 
 // ------------------------------------------------------------------- forward
+// The forward moves its K and V tiles global -> LDS directly (lds_dma16), one tile ahead of
+// the matrix cores, with no staging registers and no transposition work:
+//   K tile: [64 keys][64-column sub-tiles], 16-byte chunks swizzled as above; the lane that
+//           fills LDS slot (row, position p) fetches chunk p ^ (row&7) ^ ((row>>3)&7).
+//   V tile: [64 keys][D] as it lies in memory, 32-byte blocks XOR-ed with vsw(key) so that
+//           the transposing LDS read (ds_read_b64_tr_b16: lane i of a 16-lane group ends up
+//           with column i of a 4-key x 16-column block) is conflict-free; that read hands a
+//           lane four consecutive keys of its column, i.e. the V^T operand, key slots
+//           {4g..4g+3, 8+4g..8+4g+3} per 16-key step - the slots P's registers have.
+// Rows beyond the sequence are fetched from its last row (finite data): their scores are
+// masked, so they contribute exact zeros.
+template <int D> __device__ __forceinline__ int vsw(int key) { return D == 64 ? (key & 2) : ((key & 3) << 1); }
+
+template <int D, bool VLAYOUT>
+__device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ g, int ld, int row0, int row_last, unsigned lds_base,
+                                         int wave, int lane) {
+    constexpr int KB = 64 * D * 2 / 1024;         // one wavefront instruction moves 1 KiB
+#pragma unroll
+    for (int n0 = 0; n0 < KB; n0 += NT / WAVE) {
+        const int n = n0 + wave;
+        int row, col;
+        if constexpr (!VLAYOUT) {
+            row = (n & 7) * 8 + (lane >> 3);
+            col = (n >> 3) * 64 + (swz(row, lane & 7) << 3);
+        } else {
+            constexpr int CPR = D / 8;            // 16-byte pieces per row
+            row = n * (64 / CPR) + lane / CPR;
+            const int p = lane % CPR;
+            col = ((((p >> 1) ^ vsw<D>(row)) << 1) | (p & 1)) << 3;
+        }
+        lds_dma16(g + (size_t)min(row0 + row, row_last) * ld + col, lds_base + n * 1024);
+    }
+}
+
+// V^T operand: columns col0 + lane%32 of the V tile, keys of 16-step J in P's slot order.
+template <int D>
+__device__ __forceinline__ bf16x8 frag_v(const bf16_t* Vs, int col0, int J, int lane) {
+    typedef bf16x4 __attribute__((address_space(3))) * lds_v4;
+    const int i = lane & 15, g = lane >> 5;
+    const int cb = (col0 >> 4) + ((lane >> 4) & 1);
+    const int r = 16 * J + 4 * g + (i >> 2);
+    const bf16_t* p0 = Vs + r * D + ((cb ^ vsw<D>(r)) << 4) + ((i & 3) << 2);
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p0);
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p0 + 8 * D));      // keys +8: same swizzle
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                       float* __restrict__ lse, int S, int heads, float scale_log2e) {
     constexpr int KS = D / 16, OT = D / 32;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * D];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[2][64 * D];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][64 * D];
     const int H = heads * D, ld = 3 * H;
     const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;       // longest (causal) tiles first
     const int h = blockIdx.y, b = blockIdx.z;
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* Kg = base + H;
     const bf16_t* Vg = base + 2 * H;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wq0 = q0 + wave * 32, qrow = wq0 + l32;
+    const unsigned ks0 = lds_address(Ks), vs0 = lds_address(Vs);
+    constexpr unsigned TILE_BYTES = 64 * D * 2;
+
+    const int kv_end = CAUSAL ? min(S, q0 + 128) : S;
+    const int ntiles = (kv_end + 63) / 64;
+    dma_tile<D, false>(Kg, ld, 0, S - 1, ks0, wave, lane);
+    dma_tile<D, true>(Vg, ld, 0, S - 1, vs0, wave, lane);
 
     bf16x8 qf[KS];
 #pragma unroll
@@ -199,21 +254,13 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
         for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
     float m = NEG_BIG, lsum = 0.f;
 
-    const int kv_end = CAUSAL ? min(S, q0 + 128) : S;
-    const int ntiles = (kv_end + 63) / 64;
-    StraightRegs<D> rk;
-    TransRegs<D> rv;
-    load_straight<D>(rk, Kg, ld, 0, S, tid);
-    load_trans<D>(rv, Vg, ld, 0, S, tid);
-    store_straight<D>(rk, Ks[0], tid);
-    store_trans<D>(rv, Vt[0], tid);
-    __syncthreads();
-
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1, k0 = t * 64;
+        wait_vmcnt<0>();                   // this wavefront's share of tile t has landed
+        __syncthreads();                   // everyone's has; and tile t-1 is consumed, so its buffer is free
         if (t + 1 < ntiles) {
-            load_straight<D>(rk, Kg, ld, k0 + 64, S, tid);
-            load_trans<D>(rv, Vg, ld, k0 + 64, S, tid);
+            dma_tile<D, false>(Kg, ld, k0 + 64, S - 1, ks0 + (buf ^ 1) * TILE_BYTES, wave, lane);
+            dma_tile<D, true>(Vg, ld, k0 + 64, S - 1, vs0 + (buf ^ 1) * TILE_BYTES, wave, lane);
         }
         const bool live = !CAUSAL || k0 <= wq0 + 31;          // wavefront-uniform: some key is visible
         if (live) {
@@ -227,52 +274,55 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
                     s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Ks[buf], kt * 32 + l32, kk, g), qf[kk],
                                                                     s[kt], 0, 0, 0);
             }
-            const bool edge = (k0 + 63 >= S) || (CAUSAL && k0 + 63 > wq0);
+            // tiles that reach past the sequence or the diagonal mask key by key; the others skip it
+            // (wavefront-uniform branch)
+            if ((k0 + 63 >= S) || (CAUSAL && k0 + 63 > wq0)) {
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = k0 + kt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                        if (key >= S || (CAUSAL && key > qrow)) s[kt][r] = NEG_BIG;
+                    }
+            }
+            // running maximum in the scaled (log2) domain; the scale is positive, so it commutes with max
             float mx = NEG_BIG;
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = s[kt][r] * scale_log2e;
-                    if (edge) {
-                        const int key = k0 + kt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                        if (key >= S || (CAUSAL && key > qrow)) v = NEG_BIG;
-                    }
-                    s[kt][r] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, xor32(mx));
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+            mx = fmaxf(mx, xor32(mx)) * scale_log2e;
             const float m_new = fmaxf(m, mx);
-            const float alpha = exp2f(m - m_new);
             float rs = 0.f;
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float p = exp2f(s[kt][r] - m_new);
+                    // hardware exp2: arguments are <= 0 here, and flushing tiny results to zero is harmless
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][r], scale_log2e, -m_new));
                     s[kt][r] = p;
                     rs += p;
                 }
             rs += xor32(rs);
-            lsum = lsum * alpha + rs;
+            // the accumulators only need rescaling when some row's maximum moved
+            if (__builtin_amdgcn_ballot_w64(m_new != m)) {
+                const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+                lsum *= alpha;
+#pragma unroll
+                for (int t2 = 0; t2 < OT; ++t2)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[t2][r] *= alpha;
+            }
+            lsum += rs;
             m = m_new;
-#pragma unroll
-            for (int t2 = 0; t2 < OT; ++t2)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[t2][r] *= alpha;
 #pragma unroll
             for (int J = 0; J < 4; ++J) {
                 const bf16x8 pf = pack8(s[J >> 1], (J & 1) * 8);
 #pragma unroll
                 for (int t2 = 0; t2 < OT; ++t2)
-                    o[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Vt[buf], t2 * 32 + l32, J, g), pf, o[t2], 0, 0, 0);
+                    o[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_v<D>(Vs[buf], t2 * 32, J, lane), pf, o[t2], 0, 0, 0);
             }
         }
-        if (t + 1 < ntiles) {
-            store_straight<D>(rk, Ks[buf ^ 1], tid);
-            store_trans<D>(rv, Vt[buf ^ 1], tid);
-        }
-        __syncthreads();
     }
 
     if (qrow < S) {
@@ -319,28 +369,87 @@ __global__ __launch_bounds__(NT) void attn_delta_kernel(const bf16_t* __restrict
     }
 }
 
+// Backward tiles: one LDS copy [64 rows][D] per tensor serves BOTH operand forms - a straight
+// 16-byte read gives a lane 8 consecutive columns of its row (contraction over columns), the
+// transposing read gives it 4 consecutive rows of its column (contraction over rows).  The
+// 16-byte chunk c of row r sits at c ^ usw(r); usw is chosen so that both read patterns are
+// conflict-free on the 64 banks: a straight read touches 16 consecutive rows at one chunk
+// index, a transposing read 4 consecutive rows at 4 consecutive chunks.
+template <int D> __device__ __forceinline__ int usw(int r) {
+    if (D == 64) { const int h = (r >> 1) & 7; return ((h & 1) << 2) | (h & 2) | (h >> 2); }   // 128-byte rows: bit reversal of r/2
+    return ((r & 3) << 2) | ((r >> 2) & 3);                                                     // 256-byte rows
+}
+template <int D>
+__device__ __forceinline__ void dma_utile(const bf16_t* __restrict__ g, int ld, int row0, int row_last, unsigned lds_base,
+                                          int wave, int lane) {
+    constexpr int KB = 64 * D * 2 / 1024, CPR = D / 8;
+#pragma unroll
+    for (int n0 = 0; n0 < KB; n0 += NT / WAVE) {
+        const int n = n0 + wave;
+        const int row = n * (64 / CPR) + lane / CPR;
+        const int col = ((lane % CPR) ^ usw<D>(row)) << 3;
+        lds_dma16(g + (size_t)min(row0 + row, row_last) * ld + col, lds_base + n * 1024);
+    }
+}
+// rows = `row`, contraction step kk over 16 columns
+template <int D>
+__device__ __forceinline__ bf16x8 frag_us(const bf16_t* tile, int row, int kk, int g) {
+    return *reinterpret_cast<const bf16x8*>(tile + row * D + (((kk * 2 + g) ^ usw<D>(row)) << 3));
+}
+// rows = columns col0 + lane%32 of the tile, contraction over tile rows of 16-step J, in the
+// slot order {4g..4g+3, 8+4g..8+4g+3} of a transposed score tile
+template <int D>
+__device__ __forceinline__ bf16x8 frag_ut(const bf16_t* tile, int col0, int J, int lane) {
+    typedef bf16x4 __attribute__((address_space(3))) * lds_v4;
+    const int i = lane & 15, g = lane >> 5;
+    const int c = (((col0 >> 4) + ((lane >> 4) & 1)) << 1) + ((i >> 1) & 1);
+    const int r = 16 * J + 4 * g + (i >> 2);
+    const bf16_t* p0 = tile + r * D + ((c ^ usw<D>(r)) << 3) + ((i & 1) << 2);
+    const bf16_t* p1 = tile + (r + 8) * D + ((c ^ usw<D>(r + 8)) << 3) + ((i & 1) << 2);
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p0);
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p1);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // dK, dV of 128 keys (32 per wavefront), looping over 64-query tiles.
 //   S  = Q K^T (queries x keys)   P = exp2(S c - lse2)     dP = dO V^T
 //   dS = P (dP - delta)           dV^T += dO^T P           dK^T += Q^T dS (then * 1/sqrt(d))
-// The next tile's Q, dO, lse and delta are already on their way to registers while the
-// matrix cores work on the current one; each 32-query half of a tile is finished (scores
-// to dK/dV) before the next starts, which keeps the live score registers at 32.
+// The Q and dO tiles of the next step travel global -> LDS (lds_dma16) while the matrix cores
+// work on the current one; each 32-query half of a tile is finished (scores to dK/dV) before
+// the next starts, which keeps the live score registers at 32.  Rows beyond the sequence
+// repeat its last row; their P is masked to zero.
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2)))
-void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                         const float* __restrict__ lse, const float* __restrict__ delta,
-                         bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
+__global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                          const float* __restrict__ lse, const float* __restrict__ delta,
+                                                          bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
-    __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * D], Qt[64 * D], Os[64 * D], Ot[64 * D];
-    __shared__ __attribute__((aligned(16))) float lse2[64], dl[64];
+    constexpr unsigned TILE_BYTES = 64 * D * 2;
+    __shared__ __attribute__((aligned(16))) bf16_t Qs[2][64 * D], Os[2][64 * D];
+    __shared__ __attribute__((aligned(16))) float lse2[2][64], dl[2][64];
     const int H = heads * D, ld = 3 * H;
     const int j0 = blockIdx.x * 128, h = blockIdx.y, b = blockIdx.z;
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* dOg = dctx + (size_t)b * S * H + h * D;
     const size_t stat0 = ((size_t)b * heads + h) * S;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wj0 = j0 + wave * 32, jrow = wj0 + l32;
     const float c2 = scale * LOG2E;
+    const unsigned qs0 = lds_address(Qs), os0 = lds_address(Os);
+
+    const int qt0 = CAUSAL ? j0 / 64 : 0;
+    const int ntiles = (S + 63) / 64;
+    float stat = 0.f;                      // lse (threads 0..63) or delta (threads 64..127) of the next tile
+    auto fetch = [&](int t, int buf) {
+        const int i0 = t * 64;
+        dma_utile<D>(base, ld, i0, S - 1, qs0 + buf * TILE_BYTES, wave, lane);
+        dma_utile<D>(dOg, H, i0, S - 1, os0 + buf * TILE_BYTES, wave, lane);
+        if (tid < 128) {
+            const int i = i0 + (tid & 63);
+            stat = i < S ? (tid < 64 ? lse[stat0 + i] * LOG2E : delta[stat0 + i]) : 0.f;
+        }
+    };
+    fetch(qt0, 0);
 
     bf16x8 kf[KS], vf[KS];
 #pragma unroll
@@ -354,28 +463,15 @@ void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restric
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dk[t][r] = 0.f; dv[t][r] = 0.f; }
 
-    const int qt0 = CAUSAL ? j0 / 64 : 0;
-    const int ntiles = (S + 63) / 64;
-    TransRegs<D> rq, ro;
-    float stat = 0.f;                      // lse (threads 0..63) or delta (threads 64..127) of the next tile
-    auto fetch = [&](int t) {
-        const int i0 = t * 64;
-        load_trans<D>(rq, base, ld, i0, S, tid);
-        load_trans<D>(ro, dOg, H, i0, S, tid);
-        if (tid < 128) {
-            const int i = i0 + (tid & 63);
-            stat = i < S ? (tid < 64 ? lse[stat0 + i] * LOG2E : delta[stat0 + i]) : 0.f;
-        }
-    };
-    fetch(qt0);
     for (int t = qt0; t < ntiles; ++t) {
-        const int i0 = t * 64;
-        store_both<D>(rq, Qs, Qt, tid);
-        store_both<D>(ro, Os, Ot, tid);
-        if (tid < 64) lse2[tid] = stat;
-        else if (tid < 128) dl[tid - 64] = stat;
-        __syncthreads();
-        if (t + 1 < ntiles) fetch(t + 1);
+        const int i0 = t * 64, buf = (t - qt0) & 1;
+        wait_vmcnt<0>();                   // this wavefront's share of tile t (and its statistics) has arrived
+        if (tid < 64) lse2[buf][tid] = stat;
+        else if (tid < 128) dl[buf][tid - 64] = stat;
+        __syncthreads();                   // tile t complete in LDS; tile t-1 consumed by everyone
+        if (t + 1 < ntiles) fetch(t + 1, buf ^ 1);
+        const bf16_t* Qt = Qs[buf];
+        const bf16_t* Ot = Os[buf];
         const bool live = !CAUSAL || i0 + 63 >= wj0;           // some query of the tile sees some key of this wavefront
         if (live) {
             const bool edge = (i0 + 63 >= S) || (CAUSAL && i0 < wj0 + 31);
@@ -386,27 +482,31 @@ void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restric
                 for (int r = 0; r < 16; ++r) { p[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk) {
-                    p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Qs, it * 32 + l32, kk, g), kf[kk], p, 0, 0, 0);
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Os, it * 32 + l32, kk, g), vf[kk], dp, 0, 0, 0);
+                    p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_us<D>(Qt, it * 32 + l32, kk, g), kf[kk], p, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_us<D>(Ot, it * 32 + l32, kk, g), vf[kk], dp, 0, 0, 0);
                 }
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int il = it * 32 + 8 * r4 + 4 * g;       // 4 consecutive queries
-                    const float4 l4 = *reinterpret_cast<const float4*>(&lse2[il]);
-                    const float4 d4 = *reinterpret_cast<const float4*>(&dl[il]);
+                    const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][il]);
+                    const float4 d4 = *reinterpret_cast<const float4*>(&dl[buf][il]);
                     const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const int r = r4 * 4 + c;
-                        float pv = exp2f(p[r] * c2 - lv[c]);
-                        if (edge) {
-                            const int i = i0 + il + c;
-                            if (i >= S || (CAUSAL && i < jrow)) pv = 0.f;
-                        }
-                        p[r] = pv;
-                        dp[r] = pv * (dp[r] - dv4[c]);
+                        p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(p[r], c2, -lv[c]));     // hardware exp2
+                        dp[r] -= dv4[c];
                     }
                 }
+                if (edge) {                               // wavefront-uniform: only tiles on an edge mask
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int i = i0 + it * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                        if (i >= S || (CAUSAL && i < jrow)) p[r] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dp[r] *= p[r];
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int J = it * 2 + j;
@@ -414,13 +514,12 @@ void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restric
                     const bf16x8 dsf = pack8(dp, j * 8);
 #pragma unroll
                     for (int t2 = 0; t2 < OT; ++t2) {
-                        dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Ot, t2 * 32 + l32, J, g), pf, dv[t2], 0, 0, 0);
-                        dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Qt, t2 * 32 + l32, J, g), dsf, dk[t2], 0, 0, 0);
+                        dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_ut<D>(Ot, t2 * 32, J, lane), pf, dv[t2], 0, 0, 0);
+                        dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_ut<D>(Qt, t2 * 32, J, lane), dsf, dk[t2], 0, 0, 0);
                     }
                 }
             }
         }
-        __syncthreads();
     }
     if (jrow < S) {
         bf16_t* out = dqkv + ((size_t)b * S + jrow) * ld + h * D;
@@ -441,20 +540,30 @@ void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restric
 //   S^T = K Q^T (keys x queries)   P = exp2(S^T c - lse2)   dP^T = V dO^T
 //   dS^T = P (dP^T - delta)        dQ^T += K^T dS^T (then * 1/sqrt(d))
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2)))
-void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                        const float* __restrict__ lse, const float* __restrict__ delta,
-                        bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
+__global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                         const float* __restrict__ lse, const float* __restrict__ delta,
+                                                         bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * D], Kt[64 * D], Vs[64 * D];
+    constexpr unsigned TILE_BYTES = 64 * D * 2;
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * D], Vs[2][64 * D];
     const int H = heads * D, ld = 3 * H;
     const int q0 = (gridDim.x - 1 - blockIdx.x) * 128, h = blockIdx.y, b = blockIdx.z;
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* dOg = dctx + (size_t)b * S * H + h * D;
     const size_t stat0 = ((size_t)b * heads + h) * S;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wq0 = q0 + wave * 32, qrow = wq0 + l32;
     const float c2 = scale * LOG2E;
+    const unsigned ks0 = lds_address(Ks), vs0 = lds_address(Vs);
+
+    const int kv_end = CAUSAL ? min(S, q0 + 128) : S;
+    const int ntiles = (kv_end + 63) / 64;
+    auto fetch = [&](int t, int buf) {
+        dma_utile<D>(base + H, ld, t * 64, S - 1, ks0 + buf * TILE_BYTES, wave, lane);
+        dma_utile<D>(base + 2 * H, ld, t * 64, S - 1, vs0 + buf * TILE_BYTES, wave, lane);
+    };
+    fetch(0, 0);
 
     bf16x8 qf[KS], of[KS];
 #pragma unroll
@@ -470,21 +579,13 @@ void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[t][r] = 0.f;
 
-    const int kv_end = CAUSAL ? min(S, q0 + 128) : S;
-    const int ntiles = (kv_end + 63) / 64;
-    TransRegs<D> rk;
-    StraightRegs<D> rv;
-    auto fetch = [&](int t) {
-        load_trans<D>(rk, base + H, ld, t * 64, S, tid);
-        load_straight<D>(rv, base + 2 * H, ld, t * 64, S, tid);
-    };
-    fetch(0);
     for (int t = 0; t < ntiles; ++t) {
-        const int k0 = t * 64;
-        store_both<D>(rk, Ks, Kt, tid);
-        store_straight<D>(rv, Vs, tid);
+        const int k0 = t * 64, buf = t & 1;
+        wait_vmcnt<0>();
         __syncthreads();
-        if (t + 1 < ntiles) fetch(t + 1);
+        if (t + 1 < ntiles) fetch(t + 1, buf ^ 1);
+        const bf16_t* Kt = Ks[buf];
+        const bf16_t* Vt = Vs[buf];
         const bool live = !CAUSAL || k0 <= wq0 + 31;
         if (live) {
             const bool edge = (k0 + 63 >= S) || (CAUSAL && k0 + 63 > wq0);
@@ -495,28 +596,29 @@ void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict
                 for (int r = 0; r < 16; ++r) { p[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk) {
-                    p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Ks, kt * 32 + l32, kk, g), qf[kk], p, 0, 0, 0);
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Vs, kt * 32 + l32, kk, g), of[kk], dp, 0, 0, 0);
+                    p = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_us<D>(Kt, kt * 32 + l32, kk, g), qf[kk], p, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_us<D>(Vt, kt * 32 + l32, kk, g), of[kk], dp, 0, 0, 0);
                 }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float pv = exp2f(p[r] * c2 - my_lse2);
-                    if (edge) {
+                for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(p[r], c2, -my_lse2));   // hardware exp2
+                if (edge) {                               // wavefront-uniform: only tiles on an edge mask
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
                         const int key = k0 + kt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                        if (key >= S || (CAUSAL && key > qrow)) pv = 0.f;
+                        if (key >= S || (CAUSAL && key > qrow)) p[r] = 0.f;
                     }
-                    dp[r] = pv * (dp[r] - my_dl);
                 }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dp[r] = p[r] * (dp[r] - my_dl);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const bf16x8 dsf = pack8(dp, j * 8);
 #pragma unroll
                     for (int t2 = 0; t2 < OT; ++t2)
-                        dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_trans(Kt, t2 * 32 + l32, kt * 2 + j, g), dsf, dq[t2], 0, 0, 0);
+                        dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_ut<D>(Kt, t2 * 32, kt * 2 + j, lane), dsf, dq[t2], 0, 0, 0);
                 }
             }
         }
-        __syncthreads();
     }
     if (qrow < S) {
         bf16_t* out = dqkv + ((size_t)b * S + qrow) * ld + h * D;

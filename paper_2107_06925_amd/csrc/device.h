@@ -95,6 +95,22 @@ __device__ __forceinline__ float gelu_grad_f(float u, int erf_form) {
     return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * 0.79788456080286536f * (1.0f + 3.0f * 0.044715f * u * u);
 }
 
+// Global -> LDS without passing through registers: lane i of the wavefront writes the 16
+// bytes it fetches from `gptr` to LDS byte address lds_base + 16 i (lds_base must be the
+// same for the whole wavefront).  Issued through inline assembly so that the wait can be
+// counted by hand (wait_vmcnt) instead of draining every outstanding load.
+__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));     // expcnt, lgkmcnt untouched
+}
+// LDS byte address (32-bit pointer in the LDS address space) of a __shared__ object
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
+
 #define CHIMERA_LAUNCH_CHECK(what)                                                           \
     do {                                                                                     \
         hipError_t e__ = hipGetLastError();                                                  \

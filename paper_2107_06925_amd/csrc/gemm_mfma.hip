@@ -385,13 +385,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
 // Nothing can be zero-filled on this path: rows beyond the matrix are redirected to a
 // valid row (they only feed outputs that are never stored), and k must be a multiple
 // of BK (the caller falls back to the register-staged kernel otherwise).
-__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
-}
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));     // expcnt, lgkmcnt untouched
-}
 
 // One output tile; `block_id` numbers the tiles of this product.  ONLY_EPI >= 0 compiles
 // that epilogue alone.
