@@ -124,7 +124,10 @@ typedef struct {
 /* Op list of worker `rank` in execution order.  Writes min(count, cap) ops to
  * h_out (may be NULL if cap == 0) and the full count (2N) to *h_count.
  * EINVAL: unknown algo; D < 1; N < 1; rank outside [0, D); for CHIMERA_DIRECT
- * also D odd or N not a multiple of D.  ENOMEM: cap < count (list truncated). */
+ * also D odd, or N > D and not a multiple of D.  N < D (section 3.1): the micro-batches
+ * are split between the two pipelines as evenly as possible, down ids 0..ceil(N/2)-1, up
+ * ids ceil(N/2)..N-1; N = 1 runs on the down pipeline alone.
+ * ENOMEM: cap < count (list truncated). */
 int chimera_schedule(int algo, int D, int N, int rank,
                      chimera_op* h_out, size_t cap, size_t* h_count);
 

@@ -13,6 +13,9 @@ What it follows (Chimera paper, Li & Hoefler, SC'21):
   equally between the two pipelines, each pipeline runs them with the 1F1B
   strategy, and the two time tables are overlaid; with D even no slot of any
   worker receives two micro-batches.
+* Section 3.1, last paragraph: with fewer micro-batches than stages the N
+  micro-batches are divided between the two pipelines as evenly as possible
+  (N = 1: one micro-batch on one pipeline).
 * Section 3.5 "Scale to More Micro-Batches", direct concatenation: the table
   for D micro-batches is a basic unit; K = N/D units are chained so that the
   forwards of unit k+1 drop into the trailing bubbles of unit k.
@@ -130,8 +133,10 @@ def chimera_grid(D, N, f=1):
     """
     if D < 2 or D % 2:
         raise ValueError("Chimera needs an even number of stages")
-    if N < D or N % D:
-        raise ValueError("N must be a positive multiple of D")
+    if N < D:
+        return _partial_unit_grid(D, N, f)
+    if N % D:
+        raise ValueError("N must be a multiple of D, or smaller than D")
     if f < 1 or (D // 2) % f:
         raise ValueError("f must divide D/2")
     n = D // (2 * f)
@@ -149,6 +154,28 @@ def chimera_grid(D, N, f=1):
                     if cell in grid[w]:
                         raise AssertionError("merge conflict on worker %d slot %d" % (w, cell))
                     grid[w][cell] = (kind, pipe, g, s)
+    return grid
+
+
+def _partial_unit_grid(D, N, f):
+    """Fewer micro-batches than stages (section 3.1): the N micro-batches are split between
+    the two pipelines as evenly as possible (the down pipeline takes the extra one; N = 1
+    runs on the down pipeline alone), each pipeline runs its share under 1F1B, and the
+    tables are overlaid as before.  Ids: down 0 .. n_down-1, up n_down .. N-1."""
+    if N < 1:
+        raise ValueError("N must be positive")
+    if f != 1:
+        raise ValueError("N < D is defined for the two-pipeline scheme")
+    n_down = (N + 1) // 2
+    grid = [dict() for _ in range(D)]
+    for pipe, n, first in ((DOWN, n_down, 0), (UP, N - n_down, n_down)):
+        if n == 0:
+            continue
+        for (kind, m, s), t in _pipeline_table(D, n).items():
+            w = worker_of(D, 1, pipe, s)
+            if t in grid[w]:
+                raise AssertionError("merge conflict on worker %d slot %d" % (w, t))
+            grid[w][t] = (kind, pipe, first + m, s)
     return grid
 
 

@@ -41,9 +41,14 @@ struct Keyed { int64_t slot; Op op; };
 
 int build_chimera(int D, int N, int f, std::vector<std::vector<Op>>& lists) {
     if (D < 2 || (D & 1)) return fail(CHIMERA_EINVAL, "Chimera needs an even number of stages, got D=%d", D);
-    if (N < D || N % D) return fail(CHIMERA_EINVAL, "N=%d must be a positive multiple of D=%d", N, D);
+    if (N > D && N % D) return fail(CHIMERA_EINVAL, "N=%d must be a multiple of D=%d, or smaller than D", N, D);
     if (f < 1 || (D / 2) % f) return fail(CHIMERA_EINVAL, "f=%d must divide D/2=%d", f, D / 2);
-    const int n = D / (2 * f), K = N / D, span = D / f;
+    // Fewer micro-batches than stages (section 3.1): one partial unit, the micro-batches split
+    // between the two pipelines as evenly as possible (the down pipeline takes the odd one).
+    const bool partial = N < D;
+    if (partial && f != 1) return fail(CHIMERA_EINVAL, "N < D is defined for two pipelines (f=1)");
+    const int n_full = D / (2 * f), K = partial ? 1 : N / D, span = D / f;
+    const int n_down = (N + 1) / 2;
     lists.assign(D, {});
     for (int w = 0; w < D; ++w) {
         std::vector<Keyed> ops;
@@ -54,8 +59,10 @@ int build_chimera(int D, int N, int f, std::vector<std::vector<Op>>& lists) {
                 // stage of this pipeline that worker w holds
                 const int s = up ? ((i * span + D - 1 - w) % D + D) % D : ((w - i * span) % D + D) % D;
                 const int block = up ? f + i : i;           // which n ids of the unit this pipeline carries
+                const int n = partial ? (up ? N - n_down : n_down) : n_full;
+                const int first = partial ? (up ? n_down : 0) : k * D + block * n_full;
                 for (int m = 0; m < n; ++m) {
-                    const int g = k * D + block * n + m;
+                    const int g = first + m;
                     const int64_t base = (int64_t)2 * D * k + 2 * m;
                     Op fw{}; fw.kind = CHIMERA_OP_F; fw.pipe = pipe; fw.mb = g; fw.stage = s;
                     Op bw = fw; bw.kind = CHIMERA_OP_B;

@@ -83,7 +83,7 @@ def test_stash_slots_per_stage():
             assert max(d, u) <= D // 2 and d + u >= so.simulate(so.chimera_schedule(D, D), D)["stash_peak"][rank]
 
 
-@pytest.mark.parametrize("args", [(b.DIRECT, 5, 5, 0), (b.DIRECT, 4, 6, 0), (b.DIRECT, 4, 2, 0), (b.DIRECT, 4, 4, 4),
+@pytest.mark.parametrize("args", [(b.DIRECT, 5, 5, 0), (b.DIRECT, 4, 6, 0), (b.DIRECT, 4, 0, 0), (b.DIRECT, 4, 4, 4),
                                   (b.DIRECT, 4, 4, -1), (b.DIRECT, 0, 4, 0), (b.GPIPE, 4, 0, 0), (7, 4, 4, 0)])
 def test_schedule_errors(args):
     with pytest.raises(b.ChimeraError) as e:
@@ -267,3 +267,20 @@ def test_performance_model_paper_example_and_errors():
                 (b.DIRECT, 6, 6, 1, 1, 1.0, 2.0, -1.0, 0.0, 0.0, 0.0), (b.DOUBLING, 4, 8, 1, 1, 1.0, 2.0, 0.0, 0.0, 0.0, 0.0)):
         with pytest.raises(b.ChimeraError):
             b.chimera_model_iteration_time(*bad)
+
+
+@pytest.mark.parametrize("D,N", [(4, 1), (4, 2), (4, 3), (8, 1), (8, 5), (8, 6), (6, 4), (32, 7)])
+def test_fewer_micro_batches_than_stages_bit_exact(D, N):
+    want = so.chimera_schedule(D, N)
+    ref = so.simulate(want, D, 1, 1)
+    for rank in range(D):
+        got = b.chimera_schedule(b.DIRECT, D, N, rank)
+        assert [o.astuple() for o in got] == want[rank]
+        assert [o.start for o in got] == ref["start"][rank]
+    for cf, cb in ((1, 1), (1, 2)):
+        ref = so.simulate(want, D, cf, cb)
+        got = b.chimera_schedule_stats(b.DIRECT, D, N, cf, cb)
+        assert got["makespan"] == ref["makespan"] and got["bubbles"] == ref["bubbles"]
+        assert got["stash_peak"] == ref["stash_peak"] and got["critical"] == ref["critical"]
+    with pytest.raises(b.ChimeraError):
+        b.chimera_schedule_pipes(b.DIRECT, 8, 2, 2, 0)          # N < D only with two pipelines

@@ -120,6 +120,13 @@ def test_data_parallel_limit_bf16():
     _run(("dp-limit", 4, 4, 2, 1, 256, 4, 128, 2, b.BF16, False), b.DIRECT, 1)
 
 
+@pytest.mark.parametrize("N,rank", [(1, 0), (3, 1), (2, 3)])
+def test_fewer_micro_batches_than_stages(N, rank):
+    """Section 3.1: N < D; with N = 1 only the down stage exists on a worker."""
+    print("N < D", N, rank, flush=True)
+    _run(TINY, b.DIRECT, rank, N=N)
+
+
 def test_half_backwards_equal_one_backward_bitwise_outputs():
     """dx of the two halves together is bit-identical to dx of the whole backward (same kernels,
     same rows); the gradients agree to rounding (two partial sums instead of one)."""

@@ -299,3 +299,31 @@ def test_halving_with_true_costs_matches_direct():
         direct = so.simulate(so.chimera_schedule(D, D), D, 2, 4)["makespan"]
         halved = so.simulate(so.backward_halving_schedule(D, D), D, 2, 4, cost_bh=2)["makespan"]
         assert halved <= direct
+
+
+@pytest.mark.parametrize("D", [2, 4, 6, 8, 16])
+def test_fewer_micro_batches_than_stages(D):
+    """Section 3.1: N < D micro-batches are split as evenly as possible between the two
+    pipelines; N = 1 is one micro-batch on a single pipeline."""
+    for N in range(1, D):
+        lists = so.chimera_schedule(D, N)
+        n_down = sum(1 for k, p, _, _ in lists[0] if k == so.F and p == so.DOWN)
+        n_up = sum(1 for k, p, _, _ in lists[0] if k == so.F and p == so.UP)
+        assert n_down + n_up == N and 0 <= n_down - n_up <= 1
+        assert so.check_valid(lists, D, N, stages_per_worker=1 if N == 1 else 2)
+        for w, ops in enumerate(lists):
+            assert len(ops) == 2 * N
+            for kind, pipe, g, s in ops:
+                assert s == (w if pipe == so.DOWN else D - 1 - w)
+                assert (g < n_down) == (pipe == so.DOWN)
+        r = so.simulate(lists, D, 1, 1)
+        # one pipeline with n micro-batches under 1F1B ends at 2(D-1) + 2n; the longer one decides
+        assert r["makespan"] == 2 * (D - 1) + 2 * n_down
+        # it is the N = D schedule with the surplus micro-batches left out: same slots for the rest
+        full = so.simulate(so.chimera_schedule(D, D), D, 1, 1)
+        assert r["makespan"] <= full["makespan"]
+    # a single micro-batch walks down and back: 2D slots, every worker idle for all but two of them
+    r = so.simulate(so.chimera_schedule(D, 1), D, 1, 1)
+    assert r["makespan"] == 2 * D and r["bubbles"] == [2 * D - 2] * D
+    with pytest.raises(ValueError):
+        so.chimera_schedule(D, D + 1)
