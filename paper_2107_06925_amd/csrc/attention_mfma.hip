@@ -18,15 +18,10 @@
 // one query and 16 keys - exactly an operand of the next product (contraction
 // over keys) with keys {4g..4g+3, 8+4g..8+4g+3} (g = l/32) per 16-key step.
 // The other operand of that product (V^T, or Q^T, dO^T, K^T in the backward)
-// is staged in LDS transposed, with the contraction index permuted inside
-// every group of 16 so that those 8 values are one 16-byte read.  The
-// transposition happens in registers between the coalesced global load and the
-// LDS write; P never touches LDS, and no transposed tensor exists in HBM.
+// comes from the same LDS tile the tensor arrived in, through the transposing
+// LDS read; P never touches LDS, and no transposed tensor exists anywhere.
 // The fixed operand of a wavefront (its 32 queries, or its 32 keys and values)
 // is loaded straight from global memory into MFMA operand registers.
-//
-// LDS tiles are [rows][64] bf16 (128 bytes per row, 8 chunks of 16 bytes),
-// chunk c of row r stored at c ^ (r & 7) ^ ((r >> 3) & 7).
 #include "device.h"
 
 namespace chimera {
@@ -42,14 +37,6 @@ constexpr float NEG_BIG = -1.0e30f;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
-__device__ __forceinline__ int tile_off(int row, int chunk) { return row * 64 + swz(row, chunk) * 8; }
-
-__device__ __forceinline__ unsigned half_of(const uint4& q, int t) {
-    const unsigned w = (t >> 1) == 0 ? q.x : (t >> 1) == 1 ? q.y : (t >> 1) == 2 ? q.z : q.w;
-    return (t & 1) ? (w >> 16) : (w & 0xffffu);
-}
-
 __device__ __forceinline__ bf16x8 load_frag(const bf16_t* p, bool ok) {
     bf16x8 z;
 #pragma unroll
@@ -57,110 +44,46 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16_t* p, bool ok) {
     return ok ? *reinterpret_cast<const bf16x8*>(p) : z;
 }
 
-// ---- cooperative tile movers (all NT threads call them) --------------------
-// "Straight" tile: 64 rows x D columns of a row-major global matrix (row stride
-// ld), kept as D/64 LDS tiles [64][64] (sub-tile s = columns 64s..64s+63).
-template <int D> struct StraightRegs { uint4 v[64 * D / 8 / NT]; };
-
+// LDS tiles: one copy [64 rows][D] per tensor serves BOTH operand forms - a straight
+// 16-byte read gives a lane 8 consecutive columns of its row (contraction over columns), the
+// transposing read gives it 4 consecutive rows of its column (contraction over rows).  The
+// 16-byte chunk c of row r sits at c ^ usw(r); usw is chosen so that both read patterns are
+// conflict-free on the 64 banks: a straight read touches 16 consecutive rows at one chunk
+// index, a transposing read 4 consecutive rows at 4 consecutive chunks.
+template <int D> __device__ __forceinline__ int usw(int r) {
+    if (D == 64) { const int h = (r >> 1) & 7; return ((h & 1) << 2) | (h & 2) | (h >> 2); }   // 128-byte rows: bit reversal of r/2
+    return ((r & 3) << 2) | ((r >> 2) & 3);                                                     // 256-byte rows
+}
 template <int D>
-__device__ __forceinline__ void load_straight(StraightRegs<D>& r, const bf16_t* __restrict__ g, int ld, int row0,
-                                              int row_end, int tid) {
-    constexpr int CPR = D / 8;   // chunks per row
+__device__ __forceinline__ void dma_utile(const bf16_t* __restrict__ g, int ld, int row0, int row_last, unsigned lds_base,
+                                          int wave, int lane) {
+    constexpr int KB = 64 * D * 2 / 1024, CPR = D / 8;
 #pragma unroll
-    for (int it = 0; it < 64 * CPR / NT; ++it) {
-        const int c = tid + it * NT;
-        const int row = c / CPR, ch = c % CPR;
-        uint4 q = make_uint4(0u, 0u, 0u, 0u);
-        if (row0 + row < row_end) q = *reinterpret_cast<const uint4*>(g + (size_t)(row0 + row) * ld + ch * 8);
-        r.v[it] = q;
+    for (int n0 = 0; n0 < KB; n0 += NT / WAVE) {
+        const int n = n0 + wave;
+        const int row = n * (64 / CPR) + lane / CPR;
+        const int col = ((lane % CPR) ^ usw<D>(row)) << 3;
+        lds_dma16(g + (size_t)min(row0 + row, row_last) * ld + col, lds_base + n * 1024);
     }
 }
+// rows = `row`, contraction step kk over 16 columns
 template <int D>
-__device__ __forceinline__ void store_straight(const StraightRegs<D>& r, bf16_t* lds, int tid) {
-    constexpr int CPR = D / 8;
-#pragma unroll
-    for (int it = 0; it < 64 * CPR / NT; ++it) {
-        const int c = tid + it * NT;
-        const int row = c / CPR, ch = c % CPR;
-        *reinterpret_cast<uint4*>(lds + (ch >> 3) * 4096 + tile_off(row, ch & 7)) = r.v[it];
-    }
+__device__ __forceinline__ bf16x8 frag_us(const bf16_t* tile, int row, int kk, int g) {
+    return *reinterpret_cast<const bf16x8*>(tile + row * D + (((kk * 2 + g) ^ usw<D>(row)) << 3));
 }
-
-// "Transposed" tile: the same 64 x D global block, kept as D/64 LDS tiles
-// [64 columns][64 rows]: LDS row = global column, contraction index = global
-// row, permuted inside every 16: global row 16J + 8a + 4g + c sits at position
-// 16J + 8g + 4a + c.  Unit of work: 8 columns x 4 rows (four 16-byte loads).
-template <int D> struct TransRegs {
-    static constexpr int UNITS = (D / 8) * 16;
-    static constexpr int UPT = (UNITS + NT - 1) / NT;
-    uint4 v[UPT * 4];
-};
+// rows = columns col0 + lane%32 of the tile, contraction over tile rows of 16-step J, in the
+// slot order {4g..4g+3, 8+4g..8+4g+3} of a transposed score tile
 template <int D>
-__device__ __forceinline__ void load_trans(TransRegs<D>& r, const bf16_t* __restrict__ g, int ld, int row0, int row_end,
-                                           int tid) {
-    constexpr int IG = D / 8;
-#pragma unroll
-    for (int it = 0; it < TransRegs<D>::UPT; ++it) {
-        const int u = tid + it * NT;
-        const int ig = u % IG, kg = u / IG;
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const int row = row0 + kg * 4 + rr;
-            uint4 q = make_uint4(0u, 0u, 0u, 0u);
-            if (u < TransRegs<D>::UNITS && row < row_end) q = *reinterpret_cast<const uint4*>(g + (size_t)row * ld + ig * 8);
-            r.v[it * 4 + rr] = q;
-        }
-    }
-}
-template <int D>
-__device__ __forceinline__ void store_trans(const TransRegs<D>& r, bf16_t* lds, int tid) {
-    constexpr int IG = D / 8;
-#pragma unroll
-    for (int it = 0; it < TransRegs<D>::UPT; ++it) {
-        const int u = tid + it * NT;
-        if (u >= TransRegs<D>::UNITS) continue;
-        const int ig = u % IG, kg = u / IG;
-        const int koff = kg * 4;
-        const int J = koff >> 4, a = (koff >> 3) & 1, gg = (koff >> 2) & 1;
-        const int chunk = 2 * J + gg, within = 4 * a;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int col = ig * 8 + t;             // global column = LDS row
-            const unsigned w0 = half_of(r.v[it * 4 + 0], t) | (half_of(r.v[it * 4 + 1], t) << 16);
-            const unsigned w1 = half_of(r.v[it * 4 + 2], t) | (half_of(r.v[it * 4 + 3], t) << 16);
-            *reinterpret_cast<uint2*>(lds + (col >> 6) * 4096 + tile_off(col & 63, chunk) + within) = make_uint2(w0, w1);
-        }
-    }
-}
-
-// One 64 x D global block kept BOTH ways (straight in `lds_s`, transposed in `lds_t`) from a
-// single set of loads: a thread's unit of 4 rows x 8 columns is four straight 16-byte
-// chunks as loaded, and four 8-byte transposed pieces after the register shuffle.
-template <int D>
-__device__ __forceinline__ void store_both(const TransRegs<D>& r, bf16_t* lds_s, bf16_t* lds_t, int tid) {
-    constexpr int IG = D / 8;
-#pragma unroll
-    for (int it = 0; it < TransRegs<D>::UPT; ++it) {
-        const int u = tid + it * NT;
-        if (u >= TransRegs<D>::UNITS) continue;
-        const int ig = u % IG, kg = u / IG;
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const int row = kg * 4 + rr;
-            *reinterpret_cast<uint4*>(lds_s + (ig >> 3) * 4096 + tile_off(row, ig & 7)) = r.v[it * 4 + rr];
-        }
-    }
-    store_trans<D>(r, lds_t, tid);
-}
-
-// Operand fragment of a straight tile: row `row` (0..63), contraction step kk (16 columns each).
-template <int D>
-__device__ __forceinline__ bf16x8 frag_straight(const bf16_t* lds, int row, int kk, int g) {
-    return *reinterpret_cast<const bf16x8*>(lds + (kk >> 2) * 4096 + tile_off(row, (kk & 3) * 2 + g));
-}
-// Operand fragment of a transposed tile: LDS row `col` (0..D-1), 16-step J of the contraction index.
-__device__ __forceinline__ bf16x8 frag_trans(const bf16_t* lds, int col, int J, int g) {
-    return *reinterpret_cast<const bf16x8*>(lds + (col >> 6) * 4096 + tile_off(col & 63, 2 * J + g));
+__device__ __forceinline__ bf16x8 frag_ut(const bf16_t* tile, int col0, int J, int lane) {
+    typedef bf16x4 __attribute__((address_space(3))) * lds_v4;
+    const int i = lane & 15, g = lane >> 5;
+    const int c = (((col0 >> 4) + ((lane >> 4) & 1)) << 1) + ((i >> 1) & 1);
+    const int r = 16 * J + 4 * g + (i >> 2);
+    const bf16_t* p0 = tile + r * D + ((c ^ usw<D>(r)) << 3) + ((i & 1) << 2);
+    const bf16_t* p1 = tile + (r + 8) * D + ((c ^ usw<D>(r + 8)) << 3) + ((i & 1) << 2);
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p0);
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p1);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
@@ -174,52 +97,10 @@ __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, WAVE)
 
 // ------------------------------------------------------------------- forward
 // The forward moves its K and V tiles global -> LDS directly (lds_dma16), one tile ahead of
-// the matrix cores, with no staging registers and no transposition work:
-//   K tile: [64 keys][64-column sub-tiles], 16-byte chunks swizzled as above; the lane that
-//           fills LDS slot (row, position p) fetches chunk p ^ (row&7) ^ ((row>>3)&7).
-//   V tile: [64 keys][D] as it lies in memory, 32-byte blocks XOR-ed with vsw(key) so that
-//           the transposing LDS read (ds_read_b64_tr_b16: lane i of a 16-lane group ends up
-//           with column i of a 4-key x 16-column block) is conflict-free; that read hands a
-//           lane four consecutive keys of its column, i.e. the V^T operand, key slots
-//           {4g..4g+3, 8+4g..8+4g+3} per 16-key step - the slots P's registers have.
+// the matrix cores, with no staging registers and no transposition work: K is read straight
+// (contraction over the head dimension), V with the transposing read (contraction over keys).
 // Rows beyond the sequence are fetched from its last row (finite data): their scores are
 // masked, so they contribute exact zeros.
-template <int D> __device__ __forceinline__ int vsw(int key) { return D == 64 ? (key & 2) : ((key & 3) << 1); }
-
-template <int D, bool VLAYOUT>
-__device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ g, int ld, int row0, int row_last, unsigned lds_base,
-                                         int wave, int lane) {
-    constexpr int KB = 64 * D * 2 / 1024;         // one wavefront instruction moves 1 KiB
-#pragma unroll
-    for (int n0 = 0; n0 < KB; n0 += NT / WAVE) {
-        const int n = n0 + wave;
-        int row, col;
-        if constexpr (!VLAYOUT) {
-            row = (n & 7) * 8 + (lane >> 3);
-            col = (n >> 3) * 64 + (swz(row, lane & 7) << 3);
-        } else {
-            constexpr int CPR = D / 8;            // 16-byte pieces per row
-            row = n * (64 / CPR) + lane / CPR;
-            const int p = lane % CPR;
-            col = ((((p >> 1) ^ vsw<D>(row)) << 1) | (p & 1)) << 3;
-        }
-        lds_dma16(g + (size_t)min(row0 + row, row_last) * ld + col, lds_base + n * 1024);
-    }
-}
-
-// V^T operand: columns col0 + lane%32 of the V tile, keys of 16-step J in P's slot order.
-template <int D>
-__device__ __forceinline__ bf16x8 frag_v(const bf16_t* Vs, int col0, int J, int lane) {
-    typedef bf16x4 __attribute__((address_space(3))) * lds_v4;
-    const int i = lane & 15, g = lane >> 5;
-    const int cb = (col0 >> 4) + ((lane >> 4) & 1);
-    const int r = 16 * J + 4 * g + (i >> 2);
-    const bf16_t* p0 = Vs + r * D + ((cb ^ vsw<D>(r)) << 4) + ((i & 3) << 2);
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p0);
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)(p0 + 8 * D));      // keys +8: same swizzle
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                       float* __restrict__ lse, int S, int heads, float scale_log2e) {
@@ -240,8 +121,8 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
 
     const int kv_end = CAUSAL ? min(S, q0 + 128) : S;
     const int ntiles = (kv_end + 63) / 64;
-    dma_tile<D, false>(Kg, ld, 0, S - 1, ks0, wave, lane);
-    dma_tile<D, true>(Vg, ld, 0, S - 1, vs0, wave, lane);
+    dma_utile<D>(Kg, ld, 0, S - 1, ks0, wave, lane);
+    dma_utile<D>(Vg, ld, 0, S - 1, vs0, wave, lane);
 
     bf16x8 qf[KS];
 #pragma unroll
@@ -259,8 +140,8 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
         wait_vmcnt<0>();                   // this wavefront's share of tile t has landed
         __syncthreads();                   // everyone's has; and tile t-1 is consumed, so its buffer is free
         if (t + 1 < ntiles) {
-            dma_tile<D, false>(Kg, ld, k0 + 64, S - 1, ks0 + (buf ^ 1) * TILE_BYTES, wave, lane);
-            dma_tile<D, true>(Vg, ld, k0 + 64, S - 1, vs0 + (buf ^ 1) * TILE_BYTES, wave, lane);
+            dma_utile<D>(Kg, ld, k0 + 64, S - 1, ks0 + (buf ^ 1) * TILE_BYTES, wave, lane);
+            dma_utile<D>(Vg, ld, k0 + 64, S - 1, vs0 + (buf ^ 1) * TILE_BYTES, wave, lane);
         }
         const bool live = !CAUSAL || k0 <= wq0 + 31;          // wavefront-uniform: some key is visible
         if (live) {
@@ -271,7 +152,7 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
                 for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk)
-                    s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_straight<D>(Ks[buf], kt * 32 + l32, kk, g), qf[kk],
+                    s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_us<D>(Ks[buf], kt * 32 + l32, kk, g), qf[kk],
                                                                     s[kt], 0, 0, 0);
             }
             // tiles that reach past the sequence or the diagonal mask key by key; the others skip it
@@ -320,7 +201,7 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
                 const bf16x8 pf = pack8(s[J >> 1], (J & 1) * 8);
 #pragma unroll
                 for (int t2 = 0; t2 < OT; ++t2)
-                    o[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_v<D>(Vs[buf], t2 * 32, J, lane), pf, o[t2], 0, 0, 0);
+                    o[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_ut<D>(Vs[buf], t2 * 32, J, lane), pf, o[t2], 0, 0, 0);
             }
         }
     }
@@ -367,48 +248,6 @@ __global__ __launch_bounds__(NT) void attn_delta_kernel(const bf16_t* __restrict
             delta[((size_t)(token / S) * heads + head) * S + (token % S)] = s;
         }
     }
-}
-
-// Backward tiles: one LDS copy [64 rows][D] per tensor serves BOTH operand forms - a straight
-// 16-byte read gives a lane 8 consecutive columns of its row (contraction over columns), the
-// transposing read gives it 4 consecutive rows of its column (contraction over rows).  The
-// 16-byte chunk c of row r sits at c ^ usw(r); usw is chosen so that both read patterns are
-// conflict-free on the 64 banks: a straight read touches 16 consecutive rows at one chunk
-// index, a transposing read 4 consecutive rows at 4 consecutive chunks.
-template <int D> __device__ __forceinline__ int usw(int r) {
-    if (D == 64) { const int h = (r >> 1) & 7; return ((h & 1) << 2) | (h & 2) | (h >> 2); }   // 128-byte rows: bit reversal of r/2
-    return ((r & 3) << 2) | ((r >> 2) & 3);                                                     // 256-byte rows
-}
-template <int D>
-__device__ __forceinline__ void dma_utile(const bf16_t* __restrict__ g, int ld, int row0, int row_last, unsigned lds_base,
-                                          int wave, int lane) {
-    constexpr int KB = 64 * D * 2 / 1024, CPR = D / 8;
-#pragma unroll
-    for (int n0 = 0; n0 < KB; n0 += NT / WAVE) {
-        const int n = n0 + wave;
-        const int row = n * (64 / CPR) + lane / CPR;
-        const int col = ((lane % CPR) ^ usw<D>(row)) << 3;
-        lds_dma16(g + (size_t)min(row0 + row, row_last) * ld + col, lds_base + n * 1024);
-    }
-}
-// rows = `row`, contraction step kk over 16 columns
-template <int D>
-__device__ __forceinline__ bf16x8 frag_us(const bf16_t* tile, int row, int kk, int g) {
-    return *reinterpret_cast<const bf16x8*>(tile + row * D + (((kk * 2 + g) ^ usw<D>(row)) << 3));
-}
-// rows = columns col0 + lane%32 of the tile, contraction over tile rows of 16-step J, in the
-// slot order {4g..4g+3, 8+4g..8+4g+3} of a transposed score tile
-template <int D>
-__device__ __forceinline__ bf16x8 frag_ut(const bf16_t* tile, int col0, int J, int lane) {
-    typedef bf16x4 __attribute__((address_space(3))) * lds_v4;
-    const int i = lane & 15, g = lane >> 5;
-    const int c = (((col0 >> 4) + ((lane >> 4) & 1)) << 1) + ((i >> 1) & 1);
-    const int r = 16 * J + 4 * g + (i >> 2);
-    const bf16_t* p0 = tile + r * D + ((c ^ usw<D>(r)) << 3) + ((i & 1) << 2);
-    const bf16_t* p1 = tile + (r + 8) * D + ((c ^ usw<D>(r + 8)) << 3) + ((i & 1) << 2);
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p0);
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4)p1);
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // dK, dV of 128 keys (32 per wavefront), looping over 64-query tiles.
