@@ -230,7 +230,14 @@ int chimera_bwd(chimera_stage* st, int mb);
 int chimera_bwd_half(chimera_stage* st, int mb, int half);
 
 int chimera_stage_in_flight(const chimera_stage* st);
-int chimera_stage_zero_grads(chimera_stage* st);                 /* enqueued   */
+/* Starts a new iteration: the stage's gradients count as zero from now on.  The zeroing
+ * itself is deferred - the next backward WRITES every gradient instead of accumulating
+ * (no fill pass and no read of the old values; one weight version per iteration, section 2),
+ * or, where a kernel on the path cannot overwrite, fills the buffer first.  The contents of
+ * d_grads are therefore unspecified between this call and the next chimera_bwd /
+ * chimera_bwd_half / chimera_stage_read_grads (which zero-fills if nothing ran); a caller
+ * that reads d_grads itself does so after the backwards of the iteration. */
+int chimera_stage_zero_grads(chimera_stage* st);
 /* Copies the gradient buffer to host memory and waits for the stream. */
 int chimera_stage_read_grads(chimera_stage* st, float* h_dst, size_t bytes);
 
@@ -319,11 +326,14 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind,
  * sum over k of B_p(k, j), the bias gradient that belongs to dW_p; it costs no extra pass
  * over B.  The h_* arguments are host arrays of `count` entries (read before the call
  * returns); the pointers in them are device pointers.  The C_p equal `count` calls of
- * chimera_op_gemm with epilogue 5.  EINVAL for anything else (nothing is launched). */
+ * chimera_op_gemm with epilogue 5.  overwrite != 0: C_p and bsum_p RECEIVE the products and
+ * sums (their old contents are neither read nor kept) - the first micro-batch of an
+ * iteration.  EINVAL for anything else (nothing is launched). */
 int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, int k,
                                      const void* const* h_a, const int* h_lda,
                                      const void* const* h_b, const int* h_ldb,
-                                     float* const* h_c, float* const* h_bsum, void* hip_stream);
+                                     float* const* h_c, float* const* h_bsum, int overwrite,
+                                     void* hip_stream);
 /* y = LN(x) gamma + beta; mean, rstd [rows] float are written for the backward. */
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x,
                              const void* d_gamma, const void* d_beta, void* d_y,

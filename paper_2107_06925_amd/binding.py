@@ -69,7 +69,7 @@ _SIGNATURES = {
     "chimera_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
-    "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p, _p]),
+    "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p, _i, _p]),
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_bwd_scratch_floats": (_sz, [_i, _i]),
     "chimera_op_layernorm_bwd": (_i, [_i, _i, _i] + [_p] * 11),
@@ -357,7 +357,7 @@ def chimera_op_gemm(a, b, c, m, n, k, a_kc, b_kc, epilogue=EPI_NONE, bias=None, 
                                 ws.numel() if ws is not None else 0, _stream(a)))
 
 
-def chimera_op_gemm_group_accumulate(problems, k, bsums=None):
+def chimera_op_gemm_group_accumulate(problems, k, bsums=None, overwrite=False):
     """problems: list of (a [k, m] bf16, b [k, n] bf16, c [m, n] float32) device tensors;
     bsums: optional list of float32 [n] tensors (or None) receiving += column sums of b."""
     cnt = len(problems)
@@ -370,7 +370,7 @@ def chimera_op_gemm_group_accumulate(problems, k, bsums=None):
                                                  ints([t.stride(0) for t in b]), ptrs(c),
                                                  None if bsums is None else (C.c_void_p * cnt)(
                                                      *[None if t is None else t.data_ptr() for t in bsums]),
-                                                 _stream(a[0]) if cnt else None))
+                                                 int(overwrite), _stream(a[0]) if cnt else None))
 
 
 def chimera_op_layernorm_fwd(x, gamma, beta, y, mean, rstd):

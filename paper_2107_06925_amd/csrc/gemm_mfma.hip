@@ -207,10 +207,12 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
                 for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], erf_form);
                 store8(C + idx, v);
             } else {
-                float old[8];
-                load8(Cf + idx, old);
+                if (!erf_form) {               // for this epilogue the flag means: overwrite instead of accumulate
+                    float old[8];
+                    load8(Cf + idx, old);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] += old[e];
+                    for (int e = 0; e < 8; ++e) v[e] += old[e];
+                }
                 store8(Cf + idx, v);
             }
         }
@@ -539,7 +541,7 @@ __device__ __forceinline__ void gemm_async_tile(
 #pragma unroll
             for (int b = 0; b < TN; ++b) {
                 const int col = cb0 + b * 32 + lane;
-                if (col < n) bsum[col] += v[b];
+                if (col < n) bsum[col] = erf_form ? v[b] : bsum[col] + v[b];
             }
     };
     if constexpr (WGK == 1) {
@@ -628,6 +630,7 @@ struct GemmGroup {
     int m[GROUP_MAX], n[GROUP_MAX], lda[GROUP_MAX], ldb[GROUP_MAX], tiles_m[GROUP_MAX], tiles_n[GROUP_MAX];
     int first[GROUP_MAX + 1];
     int count, k;
+    int overwrite;               // results replace C and bsum instead of being added
 };
 
 template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_KC>
@@ -638,10 +641,14 @@ __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_group_ker
         if (i < grp.count && (int)blockIdx.x >= grp.first[i]) p = i;
     gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, EPI_ACCUM_F32>(
         grp.a[p], grp.b[p], nullptr, nullptr, grp.c[p], nullptr, grp.m[p], grp.n[p], grp.k, grp.lda[p], grp.ldb[p],
-        EPI_ACCUM_F32, 0, 0, grp.tiles_m[p], grp.tiles_n[p], (int)blockIdx.x - grp.first[p], grp.bsum[p]);
+        EPI_ACCUM_F32, grp.overwrite, 0, grp.tiles_m[p], grp.tiles_n[p], (int)blockIdx.x - grp.first[p], grp.bsum[p]);
 }
 
 struct TileChoice { int bm, bn, splits; };
+
+// The kernels' `erf_form` argument: GeLU form for the GeLU epilogues; for the float-accumulate
+// epilogue it means "overwrite", which a single product never asks for.
+inline int epilogue_flag(const GemmArgs& g) { return g.epilogue == EPI_ACCUM_F32 ? 0 : g.gelu_erf; }
 
 TileChoice forced_tile() {
     TileChoice c{0, 0, 0};
@@ -682,7 +689,7 @@ int launch_layout(const GemmArgs& g, int splits, hipStream_t s) {
 #define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                              \
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, PF, AKC, BKC>), grid, block, 0, s, (const bf16_t*)g.a,  \
                        (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c, (bf16_t*)g.c2, g.m, g.n, \
-                       g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf, (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn,    \
+                       g.k, g.lda, g.ldb, g.epilogue, epilogue_flag(g), (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn,    \
                        splits, slabs, arrivals)
     if (g.a_kc && !g.b_kc) CHIMERA_GEMM_LAUNCH(true, false);
     else if (g.a_kc && g.b_kc) CHIMERA_GEMM_LAUNCH(true, true);
@@ -699,7 +706,7 @@ int launch_async(const GemmArgs& g, hipStream_t s) {
 #define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                                \
     hipLaunchKernelGGL((gemm_bf16_async_kernel<BM, BN, WGM, WGN, WGK, NS, AKC, BKC>), grid, block, 0, s,                   \
                        (const bf16_t*)g.a, (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c,        \
-                       (bf16_t*)g.c2, g.m, g.n, g.k, g.lda, g.ldb, g.epilogue, g.gelu_erf,                            \
+                       (bf16_t*)g.c2, g.m, g.n, g.k, g.lda, g.ldb, g.epilogue, epilogue_flag(g),                            \
                        (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn)
     if (g.a_kc && !g.b_kc) CHIMERA_GEMM_LAUNCH(true, false);
     else if (g.a_kc && g.b_kc) CHIMERA_GEMM_LAUNCH(true, true);
@@ -781,7 +788,7 @@ bool gemm_mfma_group_supports(int count, const GemmArgs* g) {
     return true;
 }
 
-int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, void* stream) {
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream) {
     if (!gemm_mfma_group_supports(count, g))
         return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
                     "one contraction length (a multiple of %d)", GROUP_MAX, BK);
@@ -792,7 +799,7 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, void*
     const TileChoice forced = forced_tile();
     const int tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= NUM_CUS ? 256 : 128);
     GemmGroup grp{};
-    grp.count = count; grp.k = g[0].k;
+    grp.count = count; grp.k = g[0].k; grp.overwrite = overwrite ? 1 : 0;
     int tiles = 0;
     for (int i = 0; i < count; ++i) {
         grp.a[i] = (const bf16_t*)g[i].a; grp.b[i] = (const bf16_t*)g[i].b; grp.c[i] = (float*)g[i].c;

@@ -69,9 +69,10 @@ int gemm_reference(int dtype, const GemmArgs& g, void* stream);
 int gemm_mfma_bf16(const GemmArgs& g, void* stream);
 bool gemm_mfma_supports(const GemmArgs& g);
 // `count` float-accumulating products (index-contiguous operands, one contraction length) in one launch;
-// bsum (may be null, entries may be null): bsum[p][j] += sum_k B_p(k, j), the bias gradient of a linear layer
+// bsum (may be null, entries may be null): bsum[p][j] += sum_k B_p(k, j), the bias gradient of a linear layer;
+// overwrite != 0: C_p and bsum_p receive the results instead of accumulating them
 bool gemm_mfma_group_supports(int count, const GemmArgs* g);
-int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, void* stream);
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream);
 size_t gemm_mfma_workspace_bytes(int m, int n, int splits);
 size_t gemm_mfma_workspace_need(int m, int n, int k);   // bytes the tile heuristic wants for this shape (0 = none)
 
@@ -83,7 +84,7 @@ int layernorm_fwd(int dtype, int rows, int cols, const void* x, int x_f32, const
 size_t layernorm_bwd_scratch_floats(int rows, int cols);
 int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, int x_f32, const float* mean,
                   const float* rstd, const void* gamma, const void* res, int res_f32, void* dx_lo, float* dx_hi,
-                  float* dgamma, float* dbeta, float* scratch, void* stream);
+                  float* dgamma, float* dbeta, float* scratch, int overwrite, void* stream);
 size_t colsum_scratch_floats(int rows, int cols);
 int colsum(int dtype, int rows, int cols, const void* x, float* out, float* scratch, void* stream);
 int fill_zero_f32(float* p, size_t n, void* stream);

@@ -284,9 +284,11 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void colsum_kernel(const T* __restr
 // (q, c) sums parts q, q+8, q+16, ... of column c with independent loads in
 // flight, then the 8 sub-sums are added in fixed order through LDS.
 // `split` > 0: columns [0, split) go to out, columns [split, n) to out2 (LayerNorm
-// backward keeps dgamma and dbeta partials side by side).
+// backward keeps dgamma and dbeta partials side by side).  overwrite != 0: the sums
+// replace what out / out2 held instead of being added to it.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int n,
-                                                              float* __restrict__ out, float* __restrict__ out2, int split) {
+                                                              float* __restrict__ out, float* __restrict__ out2, int split,
+                                                              int overwrite) {
     __shared__ float red[8][32];
     const int c = threadIdx.x & 31, q = threadIdx.x >> 5;
     const int i = blockIdx.x * 32 + c;
@@ -306,8 +308,8 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
         float t = red[0][c];
 #pragma unroll
         for (int k = 1; k < 8; ++k) t += red[k][c];
-        if (split > 0 && i >= split) out2[i - split] += t;
-        else out[i] += t;
+        float* dst = (split > 0 && i >= split) ? out2 + (i - split) : out + i;
+        *dst = overwrite ? t : *dst + t;
     }
 }
 
@@ -339,7 +341,7 @@ int ln_fwd_launch(int rows, int cols, const void* x, const void* gamma, const vo
 template <typename TX, typename TR, typename T>
 int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
                   const void* gamma, const void* res, void* dx_lo, float* dx_hi, float* dgamma, float* dbeta,
-                  float* scratch, hipStream_t s) {
+                  float* scratch, int overwrite, hipStream_t s) {
     constexpr int V = Elem<T>::VEC;
     const int per_lane = (cols / V + WAVE - 1) / WAVE;
     const int nblk = (rows + LNB_ROWS - 1) / LNB_ROWS;
@@ -361,7 +363,7 @@ int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float
 #undef LN_BWD_WIDE
     CHIMERA_LAUNCH_CHECK("layernorm backward");
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * cols + 31) / 32), dim3(256), 0, s, scratch, nblk, 2 * cols,
-                       dgamma, dbeta, cols);
+                       dgamma, dbeta, cols, overwrite);
     CHIMERA_LAUNCH_CHECK("layernorm backward reduce");
     return CHIMERA_OK;
 }
@@ -374,7 +376,7 @@ int colsum_launch(int rows, int cols, const void* x, float* out, float* scratch,
     hipLaunchKernelGGL((colsum_kernel<T>), grid, block, 0, s, (const T*)x, scratch, rows, cols);
     CHIMERA_LAUNCH_CHECK("column sum");
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, scratch, nparts, cols, out,
-                       (float*)nullptr, 0);
+                       (float*)nullptr, 0, 0);
     CHIMERA_LAUNCH_CHECK("column sum reduce");
     return CHIMERA_OK;
 }
@@ -403,11 +405,11 @@ size_t layernorm_bwd_scratch_floats(int rows, int cols) {
 
 int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, int x_f32, const float* mean,
                   const float* rstd, const void* gamma, const void* res, int res_f32, void* dx_lo, float* dx_hi,
-                  float* dgamma, float* dbeta, float* scratch, void* stream) {
+                  float* dgamma, float* dbeta, float* scratch, int overwrite, void* stream) {
     if (int rc = check_rowwise(dtype, rows, cols)) return rc;
     if (!dx_lo && !dx_hi) return fail(CHIMERA_EINVAL, "layernorm backward needs an output");
     hipStream_t s = (hipStream_t)stream;
-#define LN_BWD_ARGS rows, cols, dy, x, mean, rstd, gamma, res, dx_lo, dx_hi, dgamma, dbeta, scratch, s
+#define LN_BWD_ARGS rows, cols, dy, x, mean, rstd, gamma, res, dx_lo, dx_hi, dgamma, dbeta, scratch, overwrite, s
     if (dtype == CHIMERA_F32) return ln_bwd_launch<float, float, float>(LN_BWD_ARGS);
     if (x_f32) return res_f32 ? ln_bwd_launch<float, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<float, bf16_t, bf16_t>(LN_BWD_ARGS);
     return res_f32 ? ln_bwd_launch<bf16_t, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<bf16_t, bf16_t, bf16_t>(LN_BWD_ARGS);

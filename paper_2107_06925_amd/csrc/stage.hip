@@ -109,6 +109,10 @@ struct chimera_stage {
     std::unordered_map<int, IO> io;
     std::unordered_map<int, int> in_flight;   // micro-batch -> slot
     std::unordered_map<int, int> halves_done; // micro-batch -> halves of its backward already run
+    // chimera_stage_zero_grads only notes that the gradients are to be read as zero: the next
+    // backward then WRITES every gradient instead of accumulating (no fill pass, no read of the
+    // old values); anything else that looks at the buffer first performs the fill.
+    bool grads_pending_zero = false;
     std::vector<char> slot_used;
 
     const char* W(int l, size_t off) const { return weights + ((size_t)l * layer_params + off) * esz; }
@@ -206,11 +210,18 @@ int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const vo
 bool wgrad_group_ok(const chimera_stage* st, const GemmArgs (&g)[4]) {
     return st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_group_supports(4, g);
 }
-int wgrad_group(chimera_stage* st, const GemmArgs (&g)[4], float* const (&db)[4], hipStream_t stream) {
+int wgrad_group(chimera_stage* st, const GemmArgs (&g)[4], float* const (&db)[4], int overwrite, hipStream_t stream) {
     double flop = 0;
     for (const GemmArgs& a : g) flop += 2.0 * a.m * a.n * a.k;
     ProfScope prof(PC_GEMM_WGRAD, flop, stream);
-    return gemm_mfma_bf16_group(4, g, db, stream);
+    return gemm_mfma_bf16_group(4, g, db, overwrite, stream);
+}
+
+// Performs a zeroing that chimera_stage_zero_grads deferred.
+int flush_pending_zero(chimera_stage* st) {
+    if (!st->grads_pending_zero) return CHIMERA_OK;
+    st->grads_pending_zero = false;
+    return fill_zero_f32(st->grads, st->layer_params * st->L, st->stream);
 }
 
 int attn_args(chimera_stage* st, AttnArgs& a) {
@@ -241,11 +252,12 @@ int st_ln_fwd(chimera_stage* st, const void* x, int x_f32, const void* g, const 
     return layernorm_fwd(st->dtype, st->vM, st->H, x, x_f32, g, b, y, mean, rstd, st->stream);
 }
 int st_ln_bwd(chimera_stage* st, const void* dy, const void* x, int x_f32, const float* mean, const float* rstd,
-              const void* g, const void* res, int res_f32, void* dx_lo, float* dx_hi, float* dg, float* db, float* scratch) {
+              const void* g, const void* res, int res_f32, void* dx_lo, float* dx_hi, float* dg, float* db, float* scratch,
+              int overwrite) {
     const double bytes = st->esz + (x_f32 ? 4 : st->esz) + (res_f32 ? 4 : st->esz) + (dx_lo ? st->esz : 0) + (dx_hi ? 4 : 0);
     ProfScope prof(PC_LN_BWD, (double)st->vM * st->H * bytes, st->stream);
     return layernorm_bwd(st->dtype, st->vM, st->H, dy, x, x_f32, mean, rstd, g, res, res_f32, dx_lo, dx_hi, dg, db, scratch,
-                         st->stream);
+                         overwrite, st->stream);
 }
 int st_colsum(chimera_stage* st, int cols, const void* x, float* out, float* scratch, hipStream_t stream) {
     ProfScope prof(PC_COLSUM, (double)st->vM * cols * st->esz, stream);
@@ -314,6 +326,16 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
     chimera_stage::IO io = io_full;
     io.x = shift(io_full.x, H, e); io.dy = shift(io_full.dy, H, e); io.dx = (void*)shift(io_full.dx, H, e);
     const int wide = st->dtype == CHIMERA_BF16;
+    // First backward after a deferred zeroing: every gradient is written, not accumulated -
+    // possible when all parameter gradients of a block come from kernels that can overwrite
+    // (the grouped launch and the LayerNorm reductions); otherwise the fill happens now.
+    int fresh = 0;
+    if (st->grads_pending_zero) {
+        const GemmArgs probe[4] = {wgrad_args(M, H, 4 * H, io.x, io.x, st->grads), wgrad_args(M, 4 * H, H, io.x, io.x, st->grads),
+                                   wgrad_args(M, H, H, io.x, io.x, st->grads), wgrad_args(M, 3 * H, H, io.x, io.x, st->grads)};
+        if (wgrad_group_ok(st, probe)) { fresh = 1; st->grads_pending_zero = false; }
+        else TRY(flush_pending_zero(st));
+    }
     float* scratch = (float*)(st->ws + st->w_scratch);
     float* scratch2 = (float*)(st->ws + (st->have_side ? st->w_scratch2 : st->w_scratch));
     hipStream_t gs = st->have_side ? st->side : st->stream;       // stream of the parameter gradients
@@ -355,6 +377,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
                                 wgrad_args(M, H, H, ctx, dx1, st->G(l, st->o_w_o)),
                                 wgrad_args(M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv))};
         const bool grouped = wgrad_group_ok(st, wg);
+        if (fresh && !grouped) return fail(CHIMERA_ESTATE, "internal: overwrite mode needs the grouped weight gradients");
         // y = x1 + g W2 + b2
         if (!grouped) {
             TRY(fork_to_side(st, 0));
@@ -370,7 +393,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
         }
         TRY(linear_dgrad(st, M, 4 * H, H, du, st->W(l, st->o_w_fc1), nullptr, dh, EPI_NONE));
         TRY(st_ln_bwd(st, dh, x1, wide, mean2, rstd2,
-                      st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch));
+                      st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch, fresh));
         // x1 = x + ctx Wo + bo
         if (!grouped) {
             TRY(fork_to_side(st, 2));
@@ -388,7 +411,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
         if (grouped) {
             // the bias gradients (column sums of dy, du, dx1, dqkv) come out of the same launch
             float* const db[4] = {st->G(l, st->o_b_fc2), st->G(l, st->o_b_fc1), st->G(l, st->o_b_o), st->G(l, st->o_b_qkv)};
-            TRY(wgrad_group(st, wg, db, gs));
+            TRY(wgrad_group(st, wg, db, fresh, gs));
         } else {
             TRY(st_colsum(st, 3 * H, dqkv, st->G(l, st->o_b_qkv), scratch2, gs));
             TRY(linear_wgrad(st, M, 3 * H, H, h1, dqkv, st->G(l, st->o_w_qkv), gs));
@@ -399,7 +422,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
         if (st->have_side && l + 1 <= L - 1) HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_side[(l + 1) & 1], 0));
         TRY(st_ln_bwd(st, dh, x, x_f32, mean1, rstd1,
                       st->W(l, st->o_ln1_g), wide ? (const void*)dx1f : (const void*)dx1, wide, dx, dxf,
-                      st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch));
+                      st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch, fresh));
         dy = dx;
         dyr = dxf ? (const void*)dxf : (const void*)dx;
         dyr_f32 = dxf != nullptr;
@@ -492,6 +515,7 @@ int chimera_stage_bind(chimera_stage* st, const void* d_weights, float* d_grads,
     if (!st->in_flight.empty()) return fail(CHIMERA_ESTATE, "cannot rebind with micro-batches in flight");
     st->weights = (const char*)d_weights; st->grads = d_grads; st->stash = (char*)d_stash; st->ws = (char*)d_workspace;
     st->slots = stash_slots; st->stream = (hipStream_t)hip_stream;
+    st->grads_pending_zero = false;
     st->slot_used.assign(stash_slots, 0);
     drop_side(st);
     if (st->overlap) {
@@ -585,13 +609,15 @@ int chimera_stage_in_flight(const chimera_stage* st) { return st ? (int)st->in_f
 int chimera_stage_zero_grads(chimera_stage* st) {
     if (!st) return fail(CHIMERA_EINVAL, "stage is NULL");
     if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
-    return fill_zero_f32(st->grads, st->layer_params * st->L, st->stream);
+    st->grads_pending_zero = true;           // performed by the next backward (as overwriting) or reader
+    return CHIMERA_OK;
 }
 
 int chimera_stage_read_grads(chimera_stage* st, float* h_dst, size_t bytes) {
     if (!st || !h_dst) return fail(CHIMERA_EINVAL, "NULL argument");
     if (!st->bound) return fail(CHIMERA_ESTATE, "stage is not bound");
     if (bytes < chimera_stage_grad_bytes(st)) return fail(CHIMERA_ENOMEM, "destination holds %zu bytes, need %zu", bytes, chimera_stage_grad_bytes(st));
+    TRY(flush_pending_zero(st));
     hipError_t e = hipMemcpyAsync(h_dst, st->grads, chimera_stage_grad_bytes(st), hipMemcpyDeviceToHost, st->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(st->stream);
     if (e != hipSuccess) return fail(CHIMERA_EDEVICE, "gradient readback: %s", hipGetErrorString(e));
@@ -786,7 +812,7 @@ size_t chimera_op_gemm_workspace_bytes(int m, int n, int k) { return gemm_mfma_w
 
 int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, int k, const void* const* h_a,
                                      const int* h_lda, const void* const* h_b, const int* h_ldb, float* const* h_c,
-                                     float* const* h_bsum, void* hip_stream) {
+                                     float* const* h_bsum, int overwrite, void* hip_stream) {
     if (count < 1 || count > 4) return fail(CHIMERA_EINVAL, "group of %d products (1..4)", count);
     if (!h_m || !h_n || !h_a || !h_lda || !h_b || !h_ldb || !h_c) return fail(CHIMERA_EINVAL, "NULL argument array");
     GemmArgs g[4] = {};
@@ -799,7 +825,7 @@ int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, 
         g[i].b = h_b[i]; g[i].ldb = h_ldb[i]; g[i].b_kc = 0;
         g[i].c = h_c[i]; g[i].epilogue = EPI_ACCUM_F32;
     }
-    return gemm_mfma_bf16_group(count, g, h_bsum, hip_stream);
+    return gemm_mfma_bf16_group(count, g, h_bsum, overwrite, hip_stream);
 }
 
 int chimera_op_layernorm_fwd(int dtype, int rows, int cols, const void* d_x, const void* d_gamma, const void* d_beta,
@@ -816,7 +842,7 @@ int chimera_op_layernorm_bwd(int dtype, int rows, int cols, const void* d_dy, co
     if (!d_dy || !d_x || !d_mean || !d_rstd || !d_gamma || !d_res || !d_dx || !d_dgamma || !d_dbeta || !d_scratch)
         return fail(CHIMERA_EINVAL, "NULL operand");
     return layernorm_bwd(dtype, rows, cols, d_dy, d_x, 0, d_mean, d_rstd, d_gamma, d_res, 0, d_dx, nullptr, d_dgamma, d_dbeta, d_scratch,
-                         hip_stream);
+                         0, hip_stream);
 }
 
 size_t chimera_op_colsum_scratch_floats(int rows, int cols) { return colsum_scratch_floats(rows, cols); }

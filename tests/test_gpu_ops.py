@@ -143,6 +143,30 @@ def test_gemm_group_accumulate(k, shapes, with_bsum):
             assert_close(to_np(bs[i]) - bs0[i], 2 * want_b[i], b.BF16, "column sums %d" % i)
 
 
+def test_gemm_group_overwrite():
+    """overwrite: C and the column sums receive the results whatever they held (NaN here)."""
+    import torch
+    k, shapes = 192, [(136, 264), (128, 128), (264, 136)]
+    probs, bs, want, want_b = [], [], [], []
+    for i, (m, n) in enumerate(shapes):
+        X, dY = _rand((k, m), 70 + i, b.BF16), _rand((k, n), 80 + i, b.BF16)
+        probs.append((to_dev(X, b.BF16), to_dev(dY, b.BF16), torch.full((m, n), float("nan"), device="cuda")))
+        bs.append(torch.full((n,), float("nan"), device="cuda"))
+        want.append(X.astype(np.float64).T @ dY.astype(np.float64))
+        want_b.append(dY.astype(np.float64).sum(axis=0))
+    b.chimera_op_gemm_group_accumulate(probs, k, bs, overwrite=True)
+    b.chimera_op_gemm_group_accumulate(probs, k, bs)              # and a second micro-batch accumulates
+    torch.cuda.synchronize()
+    for i, (_, _, c) in enumerate(probs):
+        assert_close(to_np(c), 2 * want[i], b.BF16, "product %d" % i)
+        assert_close(to_np(bs[i]), 2 * want_b[i], b.BF16, "column sums %d" % i)
+    # a single product with the float-accumulate epilogue never overwrites, whatever the GeLU flag says
+    X, dY, c = probs[1][0], probs[1][1], torch.ones((128, 128), device="cuda")
+    b.chimera_op_gemm(X, dY, c, 128, 128, k, 0, 0, b.EPI_ACCUM_F32, gelu_erf=True)
+    torch.cuda.synchronize()
+    assert_close(to_np(c) - 1.0, want[1], b.BF16, "accumulate with gelu flag set")
+
+
 def test_gemm_group_matches_single_launches_bitwise():
     import torch
     k, shapes = 320, [(136, 264), (264, 136), (128, 128)]

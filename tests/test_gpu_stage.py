@@ -155,3 +155,28 @@ def test_protocol_errors():
     assert L.chimera_run_worker_algo(b.GPIPE, 0, 2, 2) == b.ENOMEM
     assert L.chimera_run_worker(0, 2, 2) == b.ESTATE               # Chimera needs an up stage
     st.close()
+
+
+def test_deferred_zeroing_of_gradients():
+    """chimera_stage_zero_grads defers the fill: the next backward overwrites (matrix-core path)
+    or fills first (plain kernels); reading without a backward gives zeros; garbage left in the
+    buffer never leaks into the gradients."""
+    import torch
+    for dtype, ref in ((b.BF16, False), (b.F32, False), (b.BF16, True)):
+        L, H, heads, S, B = 2, 128, 2, 64, 2
+        gain = synth.qk_gain_for(H) if dtype == b.BF16 else 1.0
+        st, params = make_stage(L, H, heads, S, B, dtype, 0, reference_kernels=ref, qk_gain=gain)
+        x, dy = _mb(B * S, H, 0, dtype)
+        st.set_io(0, to_dev(x, dtype), to_dev(dy, dtype))
+        st.grads.fill_(float("nan"))                  # whatever an earlier iteration left behind
+        st.zero_grads()
+        assert np.all(st.read_grads() == 0.0)         # a reader sees zeros
+        st.grads.fill_(float("nan"))
+        st.zero_grads()
+        st.fwd(0); st.bwd(0)
+        st.fwd(0); st.bwd(0)                          # second micro-batch accumulates onto the first
+        torch.cuda.synchronize()
+        _, _, gr = bo.stage_pass(x, dy, params, B, S, heads, True)
+        twice = [{k: 2 * v for k, v in layer.items()} for layer in gr]
+        compare_grads(st.read_grads(), twice, L, H, dtype, "dtype %d ref %s" % (dtype, ref))
+        st.close()
