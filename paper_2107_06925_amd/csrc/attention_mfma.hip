@@ -3,10 +3,11 @@
 //
 //   forward   per (sequence, head, 128 queries): loop over 64-key tiles with an
 //             online softmax; writes ctx and the log-sum-exp of every row.
-//   backward  delta = rowsum(dctx * ctx); then two kernels that both rebuild
-//             P = exp(q k^T / sqrt(d) - lse) from the saved log-sum-exp:
-//             dK/dV per (sequence, head, 128 keys) looping over 64-query tiles,
-//             dQ    per (sequence, head, 128 queries) looping over 64-key tiles.
+//   backward  two kernels that both rebuild P = exp(q k^T / sqrt(d) - lse) from
+//             the saved log-sum-exp:
+//             dQ    per (sequence, head, 128 queries) looping over 64-key tiles;
+//                   it also forms delta = rowsum(dctx * ctx) of its queries,
+//             dK/dV per (sequence, head, 128 keys) looping over 64-query tiles.
 //             No atomics: every output element has one owner, so results are
 //             reproducible bit for bit.
 //
@@ -223,33 +224,6 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
 }
 
 // ------------------------------------------------------------------ backward
-// delta[b, h, s] = sum over the head's d columns of dctx * ctx.  One wavefront per token.
-template <int D>
-__global__ __launch_bounds__(NT) void attn_delta_kernel(const bf16_t* __restrict__ dctx, const bf16_t* __restrict__ ctx,
-                                                        float* __restrict__ delta, int batch, int S, int heads) {
-    const int H = heads * D, lane = threadIdx.x & 63;
-    const int token = blockIdx.x * (NT / WAVE) + (threadIdx.x >> 6);
-    if (token >= batch * S) return;
-    constexpr int LPH = D / 8;                   // lanes per head
-    for (int c0 = 0; c0 < H / 8; c0 += WAVE) {
-        const int c = c0 + lane;
-        float s = 0.f;
-        if (c < H / 8) {
-            float a[8], bb[8];
-            load_vec<bf16_t>(dctx + (size_t)token * H + c * 8, a);
-            load_vec<bf16_t>(ctx + (size_t)token * H + c * 8, bb);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s += a[e] * bb[e];
-        }
-#pragma unroll
-        for (int o = 1; o < LPH; o <<= 1) s += __shfl_xor(s, o, WAVE);
-        if (c < H / 8 && (lane % LPH) == 0) {
-            const int head = c / LPH;
-            delta[((size_t)(token / S) * heads + head) * S + (token % S)] = s;
-        }
-    }
-}
-
 // dK, dV of 128 keys (32 per wavefront), looping over 64-query tiles.
 //   S  = Q K^T (queries x keys)   P = exp2(S c - lse2)     dP = dO V^T
 //   dS = P (dP - delta)           dV^T += dO^T P           dK^T += Q^T dS (then * 1/sqrt(d))
@@ -380,8 +354,9 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restri
 //   dS^T = P (dP^T - delta)        dQ^T += K^T dS^T (then * 1/sqrt(d))
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                         const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
+                                                         const bf16_t* __restrict__ ctx, const float* __restrict__ lse,
+                                                         float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S,
+                                                         int heads, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
     constexpr unsigned TILE_BYTES = 64 * D * 2;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * D], Vs[2][64 * D];
@@ -411,7 +386,20 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restric
         of[kk] = load_frag(dOg + (size_t)qrow * H + kk * 16 + g * 8, qrow < S);
     }
     const float my_lse2 = qrow < S ? lse[stat0 + qrow] * LOG2E : 0.f;
-    const float my_dl = qrow < S ? delta[stat0 + qrow] : 0.f;
+    // delta = rowsum(dO * O) of this lane's query: the lane pair (l, l^32) holds the whole row
+    // of dO; the same pieces of O are fetched once.  Written out for the dK/dV kernel.
+    float my_dl = 0.f;
+    {
+        const bf16_t* Og = ctx + (size_t)b * S * H + h * D;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            const bf16x8 cf = load_frag(Og + (size_t)qrow * H + kk * 16 + g * 8, qrow < S);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) my_dl += (float)of[kk][e] * (float)cf[e];
+        }
+        my_dl += xor32(my_dl);
+        if (g == 0 && qrow < S) delta[stat0 + qrow] = my_dl;
+    }
     f32x16 dq[OT];
 #pragma unroll
     for (int t = 0; t < OT; ++t)
@@ -507,17 +495,14 @@ int attention_bwd_mfma(const AttnArgs& a, void* stream) {
     if (int rc = check(a)) return rc;
     if (((uintptr_t)a.ctx | (uintptr_t)a.dctx | (uintptr_t)a.dqkv) & 15) return fail(CHIMERA_EINVAL, "attention buffers must be 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
-    const int tokens = a.batch * a.seq;
-    const dim3 block(NT), tgrid((tokens + NT / WAVE - 1) / (NT / WAVE));
+    const dim3 block(NT);
     const dim3 grid((a.seq + 127) / 128, a.heads, a.batch);
     const float scale = 1.0f / sqrtf((float)a.head_dim);
 #define ATTN_BWD(D, C)                                                                                              \
     do {                                                                                                            \
-        hipLaunchKernelGGL((attn_delta_kernel<D>), tgrid, block, 0, s, (const bf16_t*)a.dctx, (const bf16_t*)a.ctx,   \
-                           a.delta, a.batch, a.seq, a.heads);                                                       \
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx, \
-                           a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, scale);                                 \
         hipLaunchKernelGGL((attn_bwd_dq_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx,  \
+                           (const bf16_t*)a.ctx, a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, scale);            \
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx, \
                            a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, scale);                                 \
     } while (0)
     if (a.head_dim == 64) { if (a.causal) ATTN_BWD(64, true); else ATTN_BWD(64, false); }
