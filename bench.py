@@ -9,6 +9,7 @@ before the timed region.  Prints ONE JSON line.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -50,6 +51,47 @@ def _cpu_baseline(cfg, blocks=6):
     }
 
 
+def _time_edges(cfg, dtype, vocab):
+    """The pipeline's two ends on one micro-batch of the workload (section 4.1): embedding
+    forward + backward, and final LayerNorm + vocabulary projection + cross-entropy, forward
+    and backward."""
+    import torch
+    from paper_2107_06925_amd import binding as b
+    tdt = torch.float32 if dtype == b.F32 else torch.bfloat16
+    M, H, S = cfg.tokens, cfg.hidden, cfg.seq
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    tokens = torch.randint(0, vocab, (M,), device="cuda", dtype=torch.int32, generator=gen)
+    wte = (0.02 * torch.randn((vocab, H), device="cuda", generator=gen)).to(tdt)
+    wpe = (0.02 * torch.randn((S, H), device="cuda", generator=gen)).to(tdt)
+    x = torch.empty((M, H), device="cuda", dtype=tdt)
+    dx = torch.randn((M, H), device="cuda", generator=gen).to(tdt)
+    dwte, dwpe = torch.zeros((vocab, H), device="cuda"), torch.zeros((S, H), device="cuda")
+    y = torch.randn((M, H), device="cuda", generator=gen).to(tdt)
+    g, be = torch.ones(H, device="cuda", dtype=tdt), torch.zeros(H, device="cuda", dtype=tdt)
+    w = (0.02 * torch.randn((H, vocab), device="cuda", generator=gen)).to(tdt)
+    dy, dg, db = torch.empty_like(y), torch.zeros(H, device="cuda"), torch.zeros(H, device="cuda")
+    dw, loss = torch.zeros((H, vocab), device="cuda"), torch.zeros(1, device="cuda")
+    ws = b.chimera_head_loss(y, tokens, g, be, w, 1.0 / M, dy, dg, db, dw, loss)
+
+    def timed(f, n=5):
+        f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e3
+
+    emb = timed(lambda: (b.chimera_op_embedding_fwd(tokens, S, wte, wpe, x), b.chimera_op_embedding_bwd(tokens, S, dx, dwte, dwpe)))
+    head = timed(lambda: b.chimera_head_loss(y, tokens, g, be, w, 1.0 / M, dy, dg, db, dw, loss, workspace=ws))
+    flop = 6.0 * M * H * vocab
+    loss.zero_()
+    b.chimera_head_loss(y, tokens, g, be, w, 1.0 / M, dy, dg, db, dw, loss, workspace=ws)
+    return {"vocab": vocab, "embedding_fwd_bwd_ms": emb, "head_loss_fwd_bwd_ms": head,
+            "head_gemm_TFLOP/s": flop / (head * 1e-3) / 1e12, "loss_per_token_at_init": float(loss.item()),
+            "ln_vocab": math.log(vocab)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +106,8 @@ def main():
                     help="direct concatenation (the headline workload), forward doubling with recomputation, or backward halving")
     ap.add_argument("--micro-batches", type=int, default=0, help="N (default: the workload's; doubling needs >= 2D)")
     ap.add_argument("--f", type=int, default=1, help="2f pipelines per worker (direct schedule only)")
+    ap.add_argument("--edges", action="store_true", help="also time the first stage's embedding and the last stage's head + loss")
+    ap.add_argument("--vocab", type=int, default=50304)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs one Chimera worker on ONE GPU; --gpus %d is not supported "
@@ -221,6 +265,8 @@ def main():
                                    "stream_copy_GB/s": b.chimera_probe_copy(src, dst),
                                    "note": "register-resident 32x32x16 bf16 MFMA loop on all SIMDs; 256 MiB copy, read+write"}
         del src, dst
+    if args.edges:
+        out["edges"] = _time_edges(cfg, dtype, args.vocab)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(cfg)
     print(json.dumps(out))

@@ -362,6 +362,44 @@ int chimera_op_attention_bwd(int dtype, int impl, int batch, int seq, int heads,
                              const float* d_lse, const void* d_dctx, void* d_dqkv,
                              float* d_delta, void* hip_stream);
 
+/* ------------------------------------------------------- the pipeline's two ends
+ * Section 4.1 of the paper: the first stage of a language model carries an extra embedding
+ * layer; the last stage ends in the loss.  GPT-2 reading (token + learned position table;
+ * final LayerNorm, untied vocabulary projection, cross-entropy).  All sums have a fixed order
+ * (no atomics).  Token and target ids must lie in [0, vocab); ids outside are clamped into the
+ * table (never followed out of bounds).  hidden must be a multiple of 8, and so must vocab
+ * wherever it is a matrix dimension (cross-entropy, head).
+ *
+ * x[t] = wte[token[t]] + wpe[t mod seq];  wte [vocab, hidden], wpe [seq, hidden], x [tokens, hidden]
+ * in the given dtype; d_tokens int32 [tokens], tokens a multiple of seq. */
+int chimera_op_embedding_fwd(int dtype, int tokens, int seq, int hidden, int vocab,
+                             const int32_t* d_tokens, const void* d_wte, const void* d_wpe,
+                             void* d_x, void* hip_stream);
+/* dwte[v] += sum of dx[t] over the positions t with token[t] = v (ascending t),
+ * dwpe[p] += sum of dx[b*seq + p] over the sequences b (ascending); both float. */
+int chimera_op_embedding_bwd(int dtype, int tokens, int seq, int hidden, int vocab,
+                             const int32_t* d_tokens, const void* d_dx,
+                             float* d_dwte, float* d_dwpe, void* hip_stream);
+/* In place over d_logits [rows, vocab]: z <- scale * (softmax(z) - onehot(target)) row by row,
+ * d_loss_rows[t] = scale * (logsumexp(z[t]) - z[t, target[t]]) and d_loss[0] += their sum. */
+int chimera_op_softmax_xent(int dtype, int rows, int vocab, void* d_logits, const int32_t* d_targets,
+                            float scale, float* d_loss_rows, float* d_loss, void* hip_stream);
+/* The last stage's head, forward and backward in one call (at the last stage the backward
+ * follows its forward immediately, section 3.1):
+ *   h = LayerNorm(y; lnf_g, lnf_b),  z = h W_head (W_head stored [hidden, vocab]),
+ *   d_loss[0] += scale * sum_t (logsumexp(z[t]) - z[t, target[t]]),
+ *   d_dy = dLoss/dy [tokens, hidden] (dtype),  d_dlnf_g, d_dlnf_b [hidden], d_dw_head
+ *   [hidden, vocab] (float) += their gradients.
+ * `scale` is the weight of these tokens in the mini-batch loss (1 / token count for a mean).
+ * d_workspace: chimera_head_workspace_bytes(dtype, tokens, hidden, vocab) bytes, 256-byte
+ * aligned (it holds h, the logits and their gradient).  ENOMEM if it is too small. */
+size_t chimera_head_workspace_bytes(int dtype, int tokens, int hidden, int vocab);
+int chimera_head_loss(int dtype, int tokens, int hidden, int vocab, const void* d_y,
+                      const int32_t* d_targets, const void* d_lnf_g, const void* d_lnf_b,
+                      const void* d_w_head, float scale, void* d_dy, float* d_dlnf_g,
+                      float* d_dlnf_b, float* d_dw_head, float* d_loss, void* d_workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------ measured ceilings
  * What the device sustains, to set beside the published peaks when the stage kernels'
  * rates are reported (measurement only; the hot path never calls them).

@@ -77,6 +77,11 @@ _SIGNATURES = {
     "chimera_op_colsum": (_i, [_i, _i, _i, _p, _p, _p, _p]),
     "chimera_op_attention_fwd": (_i, [_i] * 7 + [_p, _p, _p, _p]),
     "chimera_op_attention_bwd": (_i, [_i] * 7 + [_p] * 7),
+    "chimera_op_embedding_fwd": (_i, [_i] * 5 + [_p, _p, _p, _p, _p]),
+    "chimera_op_embedding_bwd": (_i, [_i] * 5 + [_p, _p, _p, _p, _p]),
+    "chimera_op_softmax_xent": (_i, [_i, _i, _i, _p, _p, C.c_float, _p, _p, _p]),
+    "chimera_head_workspace_bytes": (_sz, [_i, _i, _i, _i]),
+    "chimera_head_loss": (_i, [_i] * 4 + [_p] * 5 + [C.c_float] + [_p] * 6 + [_sz, _p]),
     "chimera_probe_mfma_bf16": (_i, [_p, _i, C.POINTER(C.c_double), _p]),
     "chimera_probe_copy": (_i, [_p, _p, _sz, C.POINTER(C.c_double), _p]),
 }
@@ -414,3 +419,29 @@ def chimera_probe_copy(src, dst):
     out = C.c_double(0)
     check(lib().chimera_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), C.byref(out), _stream(src)))
     return out.value
+
+
+def chimera_op_embedding_fwd(tokens, seq, wte, wpe, x):
+    check(lib().chimera_op_embedding_fwd(_dt(wte), tokens.numel(), seq, wte.shape[1], wte.shape[0], _ptr(tokens), _ptr(wte),
+                                         _ptr(wpe), _ptr(x), _stream(x)))
+
+
+def chimera_op_embedding_bwd(tokens, seq, dx, dwte, dwpe):
+    check(lib().chimera_op_embedding_bwd(_dt(dx), tokens.numel(), seq, dx.shape[1], dwte.shape[0], _ptr(tokens), _ptr(dx),
+                                         _ptr(dwte), _ptr(dwpe), _stream(dx)))
+
+
+def chimera_op_softmax_xent(logits, targets, scale, loss_rows, loss):
+    check(lib().chimera_op_softmax_xent(_dt(logits), logits.shape[0], logits.shape[1], _ptr(logits), _ptr(targets), scale,
+                                        _ptr(loss_rows), _ptr(loss), _stream(logits)))
+
+
+def chimera_head_loss(y, targets, lnf_g, lnf_b, w_head, scale, dy, dlnf_g, dlnf_b, dw_head, loss, workspace=None):
+    """w_head [hidden, vocab]; allocates the workspace (a torch uint8 tensor) unless one is given."""
+    import torch
+    need = lib().chimera_head_workspace_bytes(_dt(y), y.shape[0], y.shape[1], w_head.shape[1])
+    ws = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device=y.device)
+    check(lib().chimera_head_loss(_dt(y), y.shape[0], y.shape[1], w_head.shape[1], _ptr(y), _ptr(targets), _ptr(lnf_g),
+                                  _ptr(lnf_b), _ptr(w_head), scale, _ptr(dy), _ptr(dlnf_g), _ptr(dlnf_b), _ptr(dw_head),
+                                  _ptr(loss), _ptr(ws), ws.numel(), _stream(y)))
+    return ws

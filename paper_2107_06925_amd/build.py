@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libchimera.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["schedule.cpp", "stage.hip", "rowwise.hip", "reference_kernels.hip", "gemm_mfma.hip", "attention_mfma.hip", "probe.hip"]
+SOURCES = ["schedule.cpp", "stage.hip", "rowwise.hip", "reference_kernels.hip", "gemm_mfma.hip", "attention_mfma.hip", "probe.hip", "edges.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

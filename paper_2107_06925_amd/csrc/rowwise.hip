@@ -128,7 +128,10 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
             const int c = lane + t * WAVE;
             if (c < nchunk) {
                 float rv[V], o[V];
-                load_elems<TR, V>(res + (size_t)row * cols + c * V, rv);
+                if (res) load_elems<TR, V>(res + (size_t)row * cols + c * V, rv);       // no residual path: dx = LN'(dy)
+                else
+#pragma unroll
+                    for (int e = 0; e < V; ++e) rv[e] = 0.f;
 #pragma unroll
                 for (int e = 0; e < V; ++e) o[e] = rv[e] + rs * (dxh[t][e] - m1 - xh[t][e] * m2);
                 if (dx_lo) store_vec<T>(dx_lo + (size_t)row * cols + c * V, o);
@@ -222,7 +225,10 @@ __global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __res
             const int c = tid + t * LNW_THREADS;
             if (c < nchunk) {
                 float rv[V], o[V];
-                load_elems<TR, V>(res + (size_t)row * cols + c * V, rv);
+                if (res) load_elems<TR, V>(res + (size_t)row * cols + c * V, rv);       // no residual path: dx = LN'(dy)
+                else
+#pragma unroll
+                    for (int e = 0; e < V; ++e) rv[e] = 0.f;
 #pragma unroll
                 for (int e = 0; e < V; ++e) o[e] = rv[e] + rs * (dxh[t][e] - m1 - xh[t][e] * m2);
                 if (dx_lo) store_vec<T>(dx_lo + (size_t)row * cols + c * V, o);
