@@ -25,6 +25,10 @@ STAGE_CASES = [
     (2, 128, 2, 96, 2, b.BF16, True, False, False, synth.qk_gain_for(128)),     # bf16, matrix-core kernels, d = 64
     (2, 256, 2, 160, 1, b.BF16, False, False, False, synth.qk_gain_for(256)),   # d = 128, bidirectional
     (3, 320, 5, 200, 2, b.BF16, True, True, False, synth.qk_gain_for(320)),     # hidden not a multiple of 128, ragged seq
+    (2, 64, 1, 1, 1, b.F32, True, False, False, 1.0),          # degenerate: one token, one head
+    (2, 64, 1, 1, 1, b.BF16, True, False, False, 1.0),
+    (1, 128, 2, 3, 5, b.BF16, False, False, False, synth.qk_gain_for(128)),     # 15 tokens: fewer rows than any tile
+    (1, 128, 1, 129, 1, b.BF16, True, False, False, synth.qk_gain_for(128)),    # d = 128, one row past two attention tiles
 ]
 
 
