@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the grouped weight-gradient kernel, from two rocprofv3 --pmc runs of
 # this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the kernel's
 # launches), each scaled by what the same counter reads for a streaming kernel of known size
-# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (209987.7 * 2.00 + 49188.1) KiB.
-WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((209987.7 * 2.00 + 49188.1) * 1024)}
+# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (196140.5 * 2.00 + 49188.3) KiB.
+WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((196140.5 * 2.00 + 49188.3) * 1024)}
 
 
 def _cpu_baseline(cfg, blocks=6):
