@@ -24,6 +24,19 @@ HBM_PEAK_GBS = 8000.0
 # this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the kernel's
 # launches), each scaled by what the same counter reads for a streaming kernel of known size
 # (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (196140.5 * 2.00 + 49188.3) KiB.
+
+
+def _group_kernel_params(hidden):
+    """Template arguments of the grouped weight-gradient kernel the library picks for a block of this width
+    (its rule: 256x256 tiles once the four products have 160 of them, else 128x128; the 128x128 form is
+    k-sliced over 8 wavefronts below 512 tiles)."""
+    t = lambda n, tile: -(-n // tile)
+    shapes = [(hidden, 3 * hidden), (hidden, hidden), (hidden, 4 * hidden), (4 * hidden, hidden)]
+    if sum(t(m, 256) * t(n, 256) for m, n in shapes) >= 160:
+        return "256,256,2,4,1,2"
+    return "128,128,2,2,2,3" if sum(t(m, 128) * t(n, 128) for m, n in shapes) < 512 else "128,128,2,2,1,2"
+
+
 WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((196140.5 * 2.00 + 49188.3) * 1024)}
 
 
@@ -202,8 +215,9 @@ def main():
         wg = prof["gemm_wgrad"]
         achieved = wg["work"] / (wg["ms"] * 1e-3) / 1e12 if wg["ms"] else 0.0
         out["roofline"] = {
-            "kernel": ("gemm_bf16_async_group_kernel<128,128,2,2,1,2,0,0> (the four weight gradients of a block, "
+            "kernel": ("gemm_bf16_async_group_kernel<%s,0,0> (the four weight gradients of a block, "
                        "dW += X^T dY in fp32, and their bias gradients, one launch per block and micro-batch)"
+                       % _group_kernel_params(cfg.hidden)
                        if dtype == b.BF16 else "gemm_ref_kernel (weight-gradient GEMMs)"),
             "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / MFMA_BF16_PEAK_TFLOPS,

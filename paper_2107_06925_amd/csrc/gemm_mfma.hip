@@ -792,12 +792,15 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int o
     if (!gemm_mfma_group_supports(count, g))
         return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
                     "one contraction length (a multiple of %d)", GROUP_MAX, BK);
-    // tile choice as for single products: 256x256 once such tiles fill the chip, else 128x128
+    // tile choice as for single products: 256x256 once such tiles occupy most of the chip, else
+    // 128x128.  (192 tiles of 256x256 on 256 CUs beat 768 tiles of 128x128: they pull half the
+    // bytes from L2 into LDS, which is what limits these kernels, and the CUs they leave free
+    // serve the launches of the other stream.)
     long t256 = 0;
     for (int i = 0; i < count; ++i) t256 += (long)((g[i].m + 255) / 256) * ((g[i].n + 255) / 256);
     const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");
     const TileChoice forced = forced_tile();
-    const int tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= NUM_CUS ? 256 : 128);
+    const int tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= 160 ? 256 : 128);
     GemmGroup grp{};
     grp.count = count; grp.k = g[0].k; grp.overwrite = overwrite ? 1 : 0;
     int tiles = 0;
