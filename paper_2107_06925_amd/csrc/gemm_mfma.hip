@@ -395,7 +395,7 @@ __device__ __forceinline__ void gemm_async_tile(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
     int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n, int block_id,
-    float* __restrict__ bsum = nullptr) {
+    float* __restrict__ bsum = nullptr, bool xcd_remap = true) {
     constexpr int NT = WGM * WGN * WGK * 64;
     constexpr int KSUB = BK / 16 / WGK;                                   // 16-wide k slices per wavefront and step
     static_assert(KSUB >= 1 && KSUB * WGK * 16 == BK, "k split must divide the step");
@@ -406,8 +406,9 @@ __device__ __forceinline__ void gemm_async_tile(
     __shared__ __attribute__((aligned(16))) bf16_t lds[NS * STAGE];
 
     const int nblk = tiles_m * tiles_n;
+    // `block_id` as the hardware deals it (round-robin over the XCDs) or already renumbered
     const int xcd = block_id & 7, local = block_id >> 3;
-    const int pid = xcd * (nblk >> 3) + min(xcd, nblk & 7) + local;
+    const int pid = xcd_remap ? xcd * (nblk >> 3) + min(xcd, nblk & 7) + local : block_id;
     const int width = GROUP_M * tiles_n;
     const int first_m = (pid / width) * GROUP_M;
     const int gsz = min(tiles_m - first_m, GROUP_M);
@@ -635,13 +636,18 @@ struct GemmGroup {
 
 template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_group_kernel(GemmGroup grp) {
+    // each XCD takes a contiguous range of the group's tiles (products laid end to end), so that
+    // its L2 sees few operand panels: one product's tiles are not dealt over all eight XCDs
+    const int total = grp.first[grp.count];
+    const int xcd = (int)blockIdx.x & 7, local = (int)blockIdx.x >> 3;
+    const int gid = xcd * (total >> 3) + min(xcd, total & 7) + local;
     int p = 0;
 #pragma unroll
     for (int i = 1; i < GROUP_MAX; ++i)
-        if (i < grp.count && (int)blockIdx.x >= grp.first[i]) p = i;
+        if (i < grp.count && gid >= grp.first[i]) p = i;
     gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, EPI_ACCUM_F32>(
         grp.a[p], grp.b[p], nullptr, nullptr, grp.c[p], nullptr, grp.m[p], grp.n[p], grp.k, grp.lda[p], grp.ldb[p],
-        EPI_ACCUM_F32, grp.overwrite, 0, grp.tiles_m[p], grp.tiles_n[p], (int)blockIdx.x - grp.first[p], grp.bsum[p]);
+        EPI_ACCUM_F32, grp.overwrite, 0, grp.tiles_m[p], grp.tiles_n[p], gid - grp.first[p], grp.bsum[p], false);
 }
 
 struct TileChoice { int bm, bn, splits; };
