@@ -40,6 +40,17 @@ bubble between the completion of their first stage and the end of their
 computation while the outer workers do.  PARITY UNPINNED by the paper: which
 idle interval serves which replica (regions (a), (b), (c) of the missing
 figure); the rule above is this file's reading.
+
+Configuration selection (section 3.4, first and last paragraphs; section 4.3):
+for every candidate (W, D) the micro-batch size is the largest one whose
+memory fits the device (greedy), and among those the configuration with the
+smallest modelled time per sample wins.  Memory of a worker (section 3.1 and
+Table 2): the stage replicas it keeps (2f for Chimera, one otherwise), M_theta
+each, plus M_a per micro-batch whose activations it holds at the worst moment
+of the schedule.  Pinned by the tests against Table 2's intervals
+([(D/2+1) M_a, D M_a] with 2 M_theta for Chimera, N M_a for GPipe, [M_a, D M_a]
+for 1F1B) and on hand-built candidate sets; the candidate sets, the tie rule
+(first candidate wins) and N = mini-batch / (W B) are this file's reading.
 """
 import math
 
@@ -118,3 +129,63 @@ def iteration_time(lists, D, W, f_t, b_t, alpha, beta, act_words, grad_words, re
     rest = [unoverlapped(r, sim["makespan"], ar, eager) for r in regions]
     return dict(T=compute + max(rest), compute=f_t * c_f + b_t * c_b, p2p=(c_f + c_b) * p2p, c_f=c_f, c_b=c_b,
                 allreduce=ar, unoverlapped=rest, comm_p2p=p2p)
+
+
+def schedule_for(algo, D, N, f=1):
+    """(op lists, stage replicas per pipeline group, stage replicas per worker) of a named schedule."""
+    if algo == "chimera":
+        return so.chimera_schedule(D, N, f), 2 * f, 2 * f
+    if algo == "gpipe":
+        return so.gpipe_schedule(D, N), 1, 1
+    if algo == "1f1b":
+        return so.one_f_one_b_schedule(D, N), 1, 1
+    raise ValueError("unknown schedule %r" % (algo,))
+
+
+def worker_memory(lists, D, replicas_on_worker, weight_bytes, act_bytes):
+    """Bytes each worker needs (section 3.1, Table 2): its stage replicas and the
+    activations of the micro-batches it holds at the worst moment."""
+    peaks = so.simulate(lists, D, 1, 1)["stash_peak"]
+    return [replicas_on_worker * weight_bytes + p * act_bytes for p in peaks]
+
+
+def select_configuration(algo, f, minibatch, capacity_bytes, alpha, beta, candidates, eager=True):
+    """Section 3.4: greedy micro-batch size per (W, D), then the best modelled throughput.
+
+    candidates: dicts with D, W, B, f_t, b_t (None: modelled from f_t), recompute,
+    act_words, grad_words, weight_bytes (M_theta of one stage replica), act_bytes
+    (M_a of one stage and micro-batch).  Returns (evaluations, best index or None);
+    an evaluation is None for a candidate whose W*B does not divide the mini-batch
+    or whose schedule does not exist, else a dict N, mem_bytes, fits, T, throughput,
+    c_f, c_b, chosen (largest fitting B of its (W, D)).
+    """
+    evals = []
+    for c in candidates:
+        per_iter = c["W"] * c["B"]
+        if per_iter < 1 or minibatch % per_iter or minibatch // per_iter < 1:
+            evals.append(None)
+            continue
+        N = minibatch // per_iter
+        try:
+            lists, per_group, per_worker = schedule_for(algo, c["D"], N, f)
+        except ValueError:
+            evals.append(None)
+            continue
+        mem = max(worker_memory(lists, c["D"], per_worker, c["weight_bytes"], c["act_bytes"]))
+        b_t = backward_time(c["f_t"], c.get("recompute", False)) if c.get("b_t") is None else c["b_t"]
+        r = iteration_time(lists, c["D"], c["W"], c["f_t"], b_t, alpha, beta, c["act_words"], c["grad_words"],
+                           per_group, eager)
+        evals.append(dict(N=N, mem_bytes=mem, fits=mem <= capacity_bytes, T=r["T"], throughput=minibatch / r["T"],
+                          c_f=r["c_f"], c_b=r["c_b"], chosen=False))
+    best = None
+    for i, (c, e) in enumerate(zip(candidates, evals)):
+        if e is None or not e["fits"]:
+            continue
+        bigger = any(e2 is not None and e2["fits"] and (c2["D"], c2["W"]) == (c["D"], c["W"]) and c2["B"] > c["B"]
+                     for c2, e2 in zip(candidates, evals))
+        if bigger:
+            continue
+        e["chosen"] = True
+        if best is None or e["throughput"] > evals[best]["throughput"]:
+            best = i
+    return evals, best

@@ -115,3 +115,83 @@ def test_chimera_beats_one_directional_schedules_in_the_model():
     dapple = pm.iteration_time(so.one_f_one_b_schedule(D, N), replicas_per_group=1, **kw)["T"]
     gpipe = pm.iteration_time(so.gpipe_schedule(D, N), replicas_per_group=1, **kw)["T"]
     assert chim < dapple <= gpipe
+
+
+# ---------------------------------------------------------------- configuration selection (section 3.4)
+
+def _cand(D, W, B, f_t=1.0, **kw):
+    c = dict(D=D, W=W, B=B, f_t=f_t, b_t=None, recompute=False, act_words=0.0, grad_words=0.0,
+             weight_bytes=10.0, act_bytes=1.0)
+    c.update(kw)
+    return c
+
+
+@pytest.mark.parametrize("D", [4, 8, 16])
+def test_worker_memory_matches_table_2(D):
+    """Table 2: Chimera keeps 2 M_theta and between (D/2+1) M_a and D M_a; GPipe M_theta and N M_a;
+    1F1B (DAPPLE) M_theta and between M_a and D M_a.  N = D micro-batches."""
+    m_theta, m_a = 1000.0, 7.0
+    lists, _, per_worker = pm.schedule_for("chimera", D, D)
+    mem = pm.worker_memory(lists, D, per_worker, m_theta, m_a)
+    assert min(mem) == 2 * m_theta + (D // 2 + 1) * m_a and max(mem) == 2 * m_theta + D * m_a
+    lists, _, per_worker = pm.schedule_for("gpipe", D, D)
+    assert set(pm.worker_memory(lists, D, per_worker, m_theta, m_a)) == {m_theta + D * m_a}
+    lists, _, per_worker = pm.schedule_for("1f1b", D, D)
+    mem = pm.worker_memory(lists, D, per_worker, m_theta, m_a)
+    assert min(mem) == m_theta + m_a and max(mem) == m_theta + D * m_a
+
+
+def test_selection_takes_the_largest_micro_batch_that_fits():
+    """Greedy rule of section 3.4: per (W, D) the largest B that fits is taken even when a smaller
+    one models faster; B = 8 does not fit here (2*10 + 4*8 = 52 > 40), B = 4 does (36)."""
+    cands = [_cand(4, 2, 1, f_t=0.9, act_bytes=1.0), _cand(4, 2, 2, f_t=1.9, act_bytes=2.0),
+             _cand(4, 2, 4, f_t=4.4, act_bytes=4.0), _cand(4, 2, 8, f_t=7.0, act_bytes=8.0)]
+    evals, best = pm.select_configuration("chimera", 1, 64, 40.0, 0.0, 0.0, cands)
+    assert [e["fits"] for e in evals] == [True, True, True, False]
+    assert [e["chosen"] for e in evals] == [False, False, True, False]
+    assert best == 2
+    assert evals[0]["throughput"] > evals[2]["throughput"]          # the smaller B would have modelled faster
+    assert evals[2]["mem_bytes"] == 2 * 10.0 + 4 * 4.0 and evals[2]["N"] == 8
+
+
+def test_selection_closed_form_without_communication():
+    """alpha = beta = 0, F_t proportional to B / D (a stage holds 1/D of the layers): with N = D the
+    iteration takes F_t (C_f + 2 C_b) with C_f = D, C_b = 2D - 2 (section 3.4's example: 6 and 10),
+    so time per sample is t0 (5D - 4) / (D^2 W) for P = W D workers: the deepest pipeline whose N
+    still equals D wins here."""
+    t0, P, minibatch = 1.0, 16, 64
+    cands = []
+    for D in (2, 4, 8):
+        W = P // D
+        B = minibatch // (W * D)                                   # N = D
+        cands.append(_cand(D, W, B, f_t=t0 * B / D))
+    evals, best = pm.select_configuration("chimera", 1, minibatch, 1e9, 0.0, 0.0, cands)
+    for c, e in zip(cands, evals):
+        D = c["D"]
+        assert e["N"] == D and (e["c_f"], e["c_b"]) == (D, 2 * D - 2)
+        assert e["T"] == pytest.approx(c["f_t"] * (D + 2 * (2 * D - 2)))
+        assert e["throughput"] == pytest.approx(minibatch / e["T"])
+    per_sample = [e["T"] / minibatch for e in evals]
+    assert best == per_sample.index(min(per_sample))
+
+
+def test_selection_skips_what_does_not_divide_or_fit():
+    cands = [_cand(4, 3, 2), _cand(4, 2, 4, weight_bytes=1e6), _cand(4, 2, 2)]
+    evals, best = pm.select_configuration("chimera", 1, 32, 100.0, 0.0, 0.0, cands)
+    assert evals[0] is None                                          # 32 % (3*2) != 0
+    assert evals[1]["fits"] is False
+    assert best == 2
+    evals, best = pm.select_configuration("chimera", 1, 32, 1.0, 0.0, 0.0, cands)
+    assert best is None
+
+
+def test_selection_evaluations_are_eq_1():
+    c = _cand(4, 2, 2, f_t=3.0, b_t=5.3, act_words=1e6, grad_words=3e8)
+    evals, _ = pm.select_configuration("chimera", 1, 32, 1e12, 5e-6, 1e-9, [c], eager=True)
+    lists = so.chimera_schedule(4, 8)
+    ref = pm.iteration_time(lists, 4, 2, 3.0, 5.3, 5e-6, 1e-9, 1e6, 3e8, 2, True)
+    assert evals[0]["T"] == ref["T"] and evals[0]["N"] == 8
+    # recomputation changes only the modelled backward time
+    c2 = _cand(4, 2, 2, f_t=3.0, recompute=True)
+    e2, _ = pm.select_configuration("1f1b", 1, 32, 1e12, 0.0, 0.0, [c2])
+    assert e2[0]["T"] == pytest.approx(pm.iteration_time(so.one_f_one_b_schedule(4, 8), 4, 2, 3.0, 9.0, 0, 0, 0, 0, 1)["T"])
