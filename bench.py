@@ -269,6 +269,27 @@ def main():
                                "allreduce_ms": m["allreduce"] * 1e3, "unoverlapped_ms": m["unoverlapped"] * 1e3,
                                "sequences_per_s_per_pipeline": N * cfg.microbatch / m["T"]}
             out["model_eq1"] = {"assumed": {"alpha_s": alpha, "beta_s_per_byte": beta, "W": 1}, **model}
+            # Section 3.4's selection of (W, D) for this model on P workers at this micro-batch size: stage
+            # times, gradient and stash sizes scale with the blocks a stage holds (measured here for
+            # cfg.layers of them); memory per stage replica = weights + fp32 gradients + fp32 Adam state.
+            if f == 1 and args.schedule == "direct":
+                P, minibatch, total_blocks = 32, 512, cfg.layers * D
+                per_block = lambda v: v / cfg.layers
+                wbytes = stages[0].weights.numel() * esz + stages[0].grads.numel() * 4 * 3
+                cands = [dict(D=d, W=P // d, B=cfg.microbatch, f_t=per_block(out["stage_times"]["F_t_ms"] * 1e-3) * total_blocks / d,
+                              b_t=per_block(out["stage_times"]["B_t_ms"] * 1e-3) * total_blocks / d, act_words=act,
+                              grad_words=per_block(grad) * total_blocks / d, weight_bytes=per_block(wbytes) * total_blocks / d,
+                              act_bytes=per_block(stages[0].slot_bytes) * total_blocks / d)
+                         for d in (2, 4, 8, 16, 32) if total_blocks % d == 0 and minibatch % ((P // d) * cfg.microbatch) == 0]
+                sel = {}
+                for name, alg in (("chimera", b.DIRECT), ("1f1b", b.ONE_F_ONE_B), ("gpipe", b.GPIPE)):
+                    ev, best = b.chimera_model_select(alg, 1, minibatch, 0.9 * 288e9, alpha, beta, cands)
+                    sel[name] = {"best": None if best is None else {"W": cands[best]["W"], "D": cands[best]["D"]},
+                                 "candidates": [{"W": c["W"], "D": c["D"], "N": e["N"], "fits": e["fits"], "T_ms": e["T"] * 1e3,
+                                                 "sequences_per_s": e["throughput"], "mem_GB": e["mem_bytes"] / 1e9}
+                                                for c, e in zip(cands, ev) if e is not None]}
+                out["model_select"] = {"assumed": {"workers": P, "minibatch": minibatch, "micro_batch": cfg.microbatch,
+                                                   "capacity_bytes": 0.9 * 288e9}, **sel}
 
     if dtype == b.BF16:
         # what this chip sustains: register-resident MFMA loop on every SIMD, and a streaming copy

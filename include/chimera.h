@@ -179,6 +179,40 @@ int chimera_model_iteration_time(int algo, int D, int N, int f, int W, double f_
                                  double alpha, double beta, double act_words, double grad_words,
                                  int eager, double* h_out);
 
+/* Configuration selection of section 3.4 (and section 4.3): a candidate is one (W, D, B) with
+ * what was measured or computed for it; P = W*D workers train a mini-batch of `minibatch`
+ * samples, so a worker runs N = minibatch / (W*B) micro-batches through its pipeline. */
+typedef struct {
+    int32_t D, W, B;        /* pipeline stages, replicated pipelines, micro-batch size            */
+    int32_t recompute;      /* activation recomputation: a backward modelled as 3 F_t, not 2 F_t   */
+    double f_t;             /* forward time of one stage at this B (section 3.4: measured)          */
+    double b_t;             /* backward time; <= 0: modelled from f_t                                */
+    double act_words;       /* one stage-boundary message                                            */
+    double grad_words;      /* gradients of one stage                                                */
+    double weight_bytes;    /* M_theta: what one stage replica keeps resident on a worker            */
+    double act_bytes;       /* M_a: activations of one stage for one micro-batch in flight           */
+} chimera_candidate;
+typedef struct {
+    int32_t valid;          /* 0: W*B does not divide the mini-batch, or the schedule does not exist */
+    int32_t N;              /* micro-batches per worker and iteration                                 */
+    int32_t fits;           /* mem_bytes <= capacity                                                  */
+    int32_t chosen;         /* the largest fitting B of its (W, D): only these compete                */
+    int32_t c_f, c_b;       /* critical path                                                          */
+    double mem_bytes;       /* worst worker: replicas * M_theta + (most micro-batches held) * M_a     */
+    double T;               /* Eq. (1)                                                                */
+    double throughput;      /* minibatch / T                                                          */
+} chimera_candidate_eval;
+/* Evaluates every candidate (memory as in section 3.1 / Table 2: 2f stage replicas per worker for
+ * CHIMERA_DIRECT, one otherwise, plus the activations held at the worst moment of the schedule;
+ * time by Eq. (1) as chimera_model_iteration_time does), keeps per (W, D) the largest B that
+ * fits `capacity_bytes` (the greedy rule of section 3.4), and returns in *h_best the index of
+ * the kept candidate with the highest throughput (the first of equals), -1 if none fits.
+ * h_eval[count] receives all evaluations.  EINVAL: count < 1, NULL arrays, a non-positive f_t,
+ * negative sizes or parameters, algo CHIMERA_DOUBLING / CHIMERA_HALVING.  Pure CPU. */
+int chimera_model_select(int algo, int f, int64_t minibatch, double capacity_bytes, double alpha, double beta,
+                         int eager, int count, const chimera_candidate* h_cand,
+                         chimera_candidate_eval* h_eval, int* h_best);
+
 /* --------------------------------------------------------------------- stage
  * A stage = `layers` Transformer blocks at fixed shape (the paper's F_t / B_t
  * black box, section 3.4).  Returns NULL on error (EINVAL: non-positive size,

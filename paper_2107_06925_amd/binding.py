@@ -67,6 +67,7 @@ _SIGNATURES = {
     "chimera_profile_enable": (_i, [_i]),
     "chimera_profile_reset": (_i, []),
     "chimera_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
+    "chimera_model_select": (_i, [_i, _i, C.c_int64, C.c_double, C.c_double, C.c_double, _i, _i, _p, _p, _p]),
     "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
     "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p, _i, _p]),
@@ -153,6 +154,34 @@ def chimera_model_iteration_time(algo, D, N, f, W, f_t, b_t, alpha, beta, act_wo
     check(lib().chimera_model_iteration_time(algo, D, N, f, W, f_t, b_t, alpha, beta, act_words, grad_words, int(eager), out))
     return {"T": out[0], "compute": out[1], "p2p": out[2], "allreduce": out[3], "unoverlapped": out[4],
             "c_f": int(out[5]), "c_b": int(out[6])}
+
+
+class Candidate(C.Structure):
+    _fields_ = [("D", C.c_int32), ("W", C.c_int32), ("B", C.c_int32), ("recompute", C.c_int32), ("f_t", C.c_double),
+                ("b_t", C.c_double), ("act_words", C.c_double), ("grad_words", C.c_double), ("weight_bytes", C.c_double),
+                ("act_bytes", C.c_double)]
+
+
+class CandidateEval(C.Structure):
+    _fields_ = [("valid", C.c_int32), ("N", C.c_int32), ("fits", C.c_int32), ("chosen", C.c_int32), ("c_f", C.c_int32),
+                ("c_b", C.c_int32), ("mem_bytes", C.c_double), ("T", C.c_double), ("throughput", C.c_double)]
+
+
+def chimera_model_select(algo, f, minibatch, capacity_bytes, alpha, beta, candidates, eager=True):
+    """candidates: dicts with the fields of chimera_candidate (b_t None or <= 0: modelled).
+    Returns (list of evaluation dicts, None for an invalid candidate; best index or None)."""
+    n = len(candidates)
+    arr = (Candidate * max(n, 1))()
+    for a, c in zip(arr, candidates):
+        a.D, a.W, a.B, a.recompute = c["D"], c["W"], c["B"], int(bool(c.get("recompute", False)))
+        a.f_t, a.b_t = c["f_t"], (c.get("b_t") or 0.0)
+        a.act_words, a.grad_words, a.weight_bytes, a.act_bytes = c["act_words"], c["grad_words"], c["weight_bytes"], c["act_bytes"]
+    ev = (CandidateEval * max(n, 1))()
+    best = C.c_int(-1)
+    check(lib().chimera_model_select(algo, f, minibatch, capacity_bytes, alpha, beta, int(eager), n, arr, ev, C.byref(best)))
+    out = [None if not e.valid else dict(N=e.N, mem_bytes=e.mem_bytes, fits=bool(e.fits), chosen=bool(e.chosen), T=e.T,
+                                          throughput=e.throughput, c_f=e.c_f, c_b=e.c_b) for e in ev[:n]]
+    return out, (None if best.value < 0 else best.value)
 
 
 def chimera_schedule_stats(algo, D, N, cost_f=1, cost_b=1):

@@ -487,3 +487,54 @@ extern "C" int chimera_model_iteration_time(int algo, int D, int N, int f, int W
     h_out[5] = r.c_f; h_out[6] = r.c_b;
     return CHIMERA_OK;
 }
+
+extern "C" int chimera_model_select(int algo, int f, int64_t minibatch, double capacity_bytes, double alpha, double beta,
+                                    int eager, int count, const chimera_candidate* h_cand,
+                                    chimera_candidate_eval* h_eval, int* h_best) {
+    if (count < 1 || !h_cand || !h_eval || !h_best) return fail(CHIMERA_EINVAL, "count must be positive and the arrays non-NULL");
+    if (minibatch < 1 || capacity_bytes < 0 || alpha < 0 || beta < 0) return fail(CHIMERA_EINVAL, "mini-batch must be positive, capacity and communication parameters non-negative");
+    if (algo != CHIMERA_DIRECT && algo != CHIMERA_GPIPE && algo != CHIMERA_1F1B) return fail(CHIMERA_EINVAL, "the model covers whole-micro-batch schedules");
+    for (int i = 0; i < count; ++i) {
+        const chimera_candidate& c = h_cand[i];
+        if (!(c.f_t > 0) || c.act_words < 0 || c.grad_words < 0 || c.weight_bytes < 0 || c.act_bytes < 0 || c.D < 1 || c.W < 1 || c.B < 1)
+            return fail(CHIMERA_EINVAL, "candidate %d: D, W, B and f_t must be positive, sizes non-negative", i);
+    }
+    const int replicas = algo == CHIMERA_DIRECT ? 2 * f : 1;        // stage replicas a worker keeps
+    for (int i = 0; i < count; ++i) {
+        const chimera_candidate& c = h_cand[i];
+        chimera_candidate_eval& e = h_eval[i];
+        e = chimera_candidate_eval{};
+        const int64_t per_iter = (int64_t)c.W * c.B;
+        if (minibatch % per_iter || minibatch / per_iter > (int64_t)1 << 20) continue;
+        const int N = (int)(minibatch / per_iter);
+        std::vector<std::vector<Op>> lists;
+        if (build_schedule(algo, c.D, N, f, lists)) continue;                 // e.g. odd D for Chimera
+        const int64_t unit[CHIMERA_OP_KINDS] = {1, 1, 1, 1, 1};
+        std::vector<std::vector<int64_t>> start, fin;
+        ReplayStatsT<int64_t> st;
+        if (replay_costs<int64_t>(lists, c.D, N, unit, start, fin, &st)) continue;
+        int peak = 0;
+        for (int32_t h : st.stash_peak_halves) peak = std::max(peak, (int)h);
+        const double b_t = c.b_t > 0 ? c.b_t : (c.recompute ? 3.0 : 2.0) * c.f_t;
+        ModelResult r{};
+        if (model_iteration(algo, c.D, N, f, c.W, c.f_t, b_t, alpha, beta, c.act_words, c.grad_words, eager, &r)) continue;
+        e.valid = 1; e.N = N; e.c_f = r.c_f; e.c_b = r.c_b;
+        e.mem_bytes = replicas * c.weight_bytes + 0.5 * peak * c.act_bytes;
+        e.fits = e.mem_bytes <= capacity_bytes;
+        e.T = r.T;
+        e.throughput = (double)minibatch / r.T;
+    }
+    int best = -1;
+    for (int i = 0; i < count; ++i) {
+        if (!h_eval[i].valid || !h_eval[i].fits) continue;
+        bool bigger = false;
+        for (int j = 0; j < count; ++j)
+            bigger = bigger || (h_eval[j].valid && h_eval[j].fits && h_cand[j].D == h_cand[i].D && h_cand[j].W == h_cand[i].W &&
+                                h_cand[j].B > h_cand[i].B);
+        if (bigger) continue;
+        h_eval[i].chosen = 1;
+        if (best < 0 || h_eval[i].throughput > h_eval[best].throughput) best = i;
+    }
+    *h_best = best;
+    return CHIMERA_OK;
+}

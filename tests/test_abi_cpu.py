@@ -269,6 +269,61 @@ def test_performance_model_paper_example_and_errors():
             b.chimera_model_iteration_time(*bad)
 
 
+def _selection_candidates(seed):
+    """A grid of (W, D, B) for P = 32 workers, Bert-48-like sizes: a stage holds 48 / D blocks."""
+    import random
+    rng = random.Random(seed)
+    P, out = 32, []
+    for D in (2, 4, 8, 16, 32, 5):                     # 5: no Chimera schedule (odd), must come back invalid
+        for B in (1, 2, 4, 8, 16, 3):
+            W = max(1, P // D)
+            blocks = 48.0 / D
+            out.append(dict(D=D, W=W, B=B, recompute=rng.random() < 0.3, f_t=1e-3 * blocks * B * (0.9 + 0.2 * rng.random()),
+                            b_t=None if rng.random() < 0.5 else 2.1e-3 * blocks * B, act_words=512.0 * 1024 * B,
+                            grad_words=12.6e6 * blocks, weight_bytes=16 * 12.6e6 * blocks, act_bytes=34.0 * 512 * 1024 * 2 * blocks * B))
+    return out
+
+
+@pytest.mark.parametrize("algo,name", [(b.DIRECT, "chimera"), (b.ONE_F_ONE_B, "1f1b"), (b.GPIPE, "gpipe")])
+@pytest.mark.parametrize("capacity", [16e9, 40e9, 1e15])
+def test_configuration_selection_matches_oracle(algo, name, capacity):
+    cands = _selection_candidates(7)
+    want, want_best = pm.select_configuration(name, 1, 512, capacity, 5e-6, 6.5e-12 * 4, cands, eager=True)
+    got, got_best = b.chimera_model_select(algo, 1, 512, capacity, 5e-6, 6.5e-12 * 4, cands, eager=True)
+    assert got_best == want_best
+    assert any(e is None for e in want)
+    if capacity < 20e9:
+        assert any(e is not None and not e["fits"] for e in want)
+    assert (want_best is not None) == any(e is not None and e["chosen"] for e in want)
+    assert want_best is not None or (name == "gpipe" and capacity < 20e9)        # GPipe holds all N micro-batches
+    for w, g in zip(want, got):
+        assert (w is None) == (g is None)
+        if w is None:
+            continue
+        assert (g["N"], g["fits"], g["chosen"], g["c_f"], g["c_b"]) == (w["N"], w["fits"], w["chosen"], w["c_f"], w["c_b"])
+        assert g["mem_bytes"] == pytest.approx(w["mem_bytes"], rel=1e-12)
+        assert g["T"] == pytest.approx(w["T"], rel=1e-12) and g["throughput"] == pytest.approx(w["throughput"], rel=1e-12)
+
+
+def test_configuration_selection_with_four_pipelines_and_errors():
+    cands = [dict(D=8, W=2, B=2, f_t=1.0, b_t=None, act_words=10.0, grad_words=100.0, weight_bytes=5.0, act_bytes=1.0),
+             dict(D=8, W=2, B=4, f_t=1.9, b_t=4.0, act_words=20.0, grad_words=100.0, weight_bytes=5.0, act_bytes=2.0)]
+    want, wb = pm.select_configuration("chimera", 2, 64, 1e9, 1e-3, 1e-4, cands)
+    got, gb = b.chimera_model_select(b.DIRECT, 2, 64, 1e9, 1e-3, 1e-4, cands)
+    assert gb == wb and [g["chosen"] for g in got] == [w["chosen"] for w in want]
+    for w, g in zip(want, got):
+        assert g["mem_bytes"] == w["mem_bytes"] and g["T"] == pytest.approx(w["T"], rel=1e-12)
+    assert got[0]["mem_bytes"] == 4 * 5.0 + 8 * 1.0                  # four stage replicas, D micro-batches held (Table 3)
+    with pytest.raises(b.ChimeraError):
+        b.chimera_model_select(b.DOUBLING, 1, 64, 1e9, 0.0, 0.0, cands)
+    with pytest.raises(b.ChimeraError):
+        b.chimera_model_select(b.DIRECT, 1, 64, 1e9, -1.0, 0.0, cands)
+    with pytest.raises(b.ChimeraError):
+        b.chimera_model_select(b.DIRECT, 1, 64, 1e9, 0.0, 0.0, [dict(cands[0], f_t=0.0)])
+    with pytest.raises(b.ChimeraError):
+        b.chimera_model_select(b.DIRECT, 1, 64, 1e9, 0.0, 0.0, [])
+
+
 @pytest.mark.parametrize("D,N", [(4, 1), (4, 2), (4, 3), (8, 1), (8, 5), (8, 6), (6, 4), (32, 7)])
 def test_fewer_micro_batches_than_stages_bit_exact(D, N):
     want = so.chimera_schedule(D, N)
