@@ -97,6 +97,32 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int first) {
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, WAVE); }
 
 // ------------------------------------------------------------------- forward
+// Which 128-row tile (by rank: 0 = the one with the most work under the causal mask), head and
+// sequence a workgroup of the 1-D grid takes; false for the padding workgroups.  Without a mask
+// the tiles of one (sequence, head) pair follow each other.  With the causal mask a tile's work
+// grows with its position, so the longest tiles of ALL pairs are dispatched first (rank slowest);
+// the pair count is padded to a multiple of 8 so that a pair always lands on the same XCD
+// (workgroup ids go round-robin over the 8 XCDs) and its K and V stay in that XCD's L2.
+template <bool CAUSAL>
+__device__ __forceinline__ bool attn_tile_of(int S, int heads, int batch, int& rank, int& h, int& b) {
+    const int T = (S + 127) / 128, bid = (int)blockIdx.x;
+    if constexpr (CAUSAL) {
+        const int pairs = heads * batch, padded = (pairs + 7) & ~7;
+        const int p = bid % padded;
+        rank = bid / padded;
+        h = p % heads; b = p / heads;
+        return p < pairs;
+    } else {
+        rank = bid % T;
+        h = (bid / T) % heads; b = bid / (T * heads);
+        return true;
+    }
+}
+inline unsigned attn_grid(const AttnArgs& a) {
+    const unsigned T = (a.seq + 127) / 128, pairs = (unsigned)a.heads * a.batch;
+    return a.causal ? T * ((pairs + 7) & ~7u) : T * pairs;
+}
+
 // The forward moves its K and V tiles global -> LDS directly (lds_dma16), one tile ahead of
 // the matrix cores, with no staging registers and no transposition work: K is read straight
 // (contraction over the head dimension), V with the transposing read (contraction over keys).
@@ -104,13 +130,15 @@ __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, WAVE)
 // masked, so they contribute exact zeros.
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
-                                                      float* __restrict__ lse, int S, int heads, float scale_log2e) {
+                                                      float* __restrict__ lse, int S, int heads, int batch,
+                                                      float scale_log2e) {
     constexpr int KS = D / 16, OT = D / 32;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * D];
     __shared__ __attribute__((aligned(16))) bf16_t Vs[2][64 * D];
     const int H = heads * D, ld = 3 * H;
-    const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;       // longest (causal) tiles first
-    const int h = blockIdx.y, b = blockIdx.z;
+    int rank, h, b;
+    if (!attn_tile_of<CAUSAL>(S, heads, batch, rank, h, b)) return;
+    const int q0 = ((S + 127) / 128 - 1 - rank) * 128;       // longest (causal) tiles first
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* Kg = base + H;
     const bf16_t* Vg = base + 2 * H;
@@ -234,13 +262,16 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                          bf16_t* __restrict__ dqkv, int S, int heads, float scale) {
+                                                          bf16_t* __restrict__ dqkv, int S, int heads, int batch,
+                                                          float scale) {
     constexpr int KS = D / 16, OT = D / 32;
     constexpr unsigned TILE_BYTES = 64 * D * 2;
     __shared__ __attribute__((aligned(16))) bf16_t Qs[2][64 * D], Os[2][64 * D];
     __shared__ __attribute__((aligned(16))) float lse2[2][64], dl[2][64];
     const int H = heads * D, ld = 3 * H;
-    const int j0 = blockIdx.x * 128, h = blockIdx.y, b = blockIdx.z;
+    int rank, h, b;
+    if (!attn_tile_of<CAUSAL>(S, heads, batch, rank, h, b)) return;
+    const int j0 = rank * 128;             // the first keys meet the most queries
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* dOg = dctx + (size_t)b * S * H + h * D;
     const size_t stat0 = ((size_t)b * heads + h) * S;
@@ -356,12 +387,14 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                          const bf16_t* __restrict__ ctx, const float* __restrict__ lse,
                                                          float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S,
-                                                         int heads, float scale) {
+                                                         int heads, int batch, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
     constexpr unsigned TILE_BYTES = 64 * D * 2;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * D], Vs[2][64 * D];
     const int H = heads * D, ld = 3 * H;
-    const int q0 = (gridDim.x - 1 - blockIdx.x) * 128, h = blockIdx.y, b = blockIdx.z;
+    int rank, h, b;
+    if (!attn_tile_of<CAUSAL>(S, heads, batch, rank, h, b)) return;
+    const int q0 = ((S + 127) / 128 - 1 - rank) * 128;
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* dOg = dctx + (size_t)b * S * H + h * D;
     const size_t stat0 = ((size_t)b * heads + h) * S;
@@ -471,6 +504,7 @@ int check(const AttnArgs& a) {
 bool attention_mfma_supports(const AttnArgs& a) {
     if (a.head_dim != 64 && a.head_dim != 128) return false;
     if (a.batch < 1 || a.seq < 1 || a.heads < 1 || a.batch > 65535 || a.heads > 65535) return false;
+    if (((unsigned long long)a.heads * a.batch + 7) * ((a.seq + 127) / 128) >= (1ull << 30)) return false;   // 1-D grid
     if ((uintptr_t)a.qkv & 15) return false;
     return true;
 }
@@ -478,12 +512,12 @@ bool attention_mfma_supports(const AttnArgs& a) {
 int attention_fwd_mfma(const AttnArgs& a, void* stream) {
     if (int rc = check(a)) return rc;
     if ((uintptr_t)a.ctx & 7) return fail(CHIMERA_EINVAL, "ctx must be 8-byte aligned");
-    const dim3 grid((a.seq + 127) / 128, a.heads, a.batch), block(NT);
+    const dim3 grid(attn_grid(a)), block(NT);
     const float sl2 = LOG2E / sqrtf((float)a.head_dim);
     hipStream_t s = (hipStream_t)stream;
 #define ATTN_FWD(D, C)                                                                                            \
     hipLaunchKernelGGL((attn_fwd_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (bf16_t*)a.ctx, a.lse, a.seq, \
-                       a.heads, sl2)
+                       a.heads, a.batch, sl2)
     if (a.head_dim == 64) { if (a.causal) ATTN_FWD(64, true); else ATTN_FWD(64, false); }
     else { if (a.causal) ATTN_FWD(128, true); else ATTN_FWD(128, false); }
 #undef ATTN_FWD
@@ -496,14 +530,14 @@ int attention_bwd_mfma(const AttnArgs& a, void* stream) {
     if (((uintptr_t)a.ctx | (uintptr_t)a.dctx | (uintptr_t)a.dqkv) & 15) return fail(CHIMERA_EINVAL, "attention buffers must be 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const dim3 block(NT);
-    const dim3 grid((a.seq + 127) / 128, a.heads, a.batch);
+    const dim3 grid(attn_grid(a));
     const float scale = 1.0f / sqrtf((float)a.head_dim);
 #define ATTN_BWD(D, C)                                                                                              \
     do {                                                                                                            \
         hipLaunchKernelGGL((attn_bwd_dq_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx,  \
-                           (const bf16_t*)a.ctx, a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, scale);            \
+                           (const bf16_t*)a.ctx, a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, a.batch, scale);   \
         hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx, \
-                           a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, scale);                                 \
+                           a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, a.batch, scale);                        \
     } while (0)
     if (a.head_dim == 64) { if (a.causal) ATTN_BWD(64, true); else ATTN_BWD(64, false); }
     else { if (a.causal) ATTN_BWD(128, true); else ATTN_BWD(128, false); }
