@@ -161,6 +161,32 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
     for (int i = threadIdx.x; i < 2 * cols; i += LN_WAVES * WAVE) out[i] = red[i];
 }
 
+// V consecutive elements of type T as they come from memory (16-byte pieces), widened later.
+template <typename T, int V> struct RawElems {
+    static constexpr int PER = Elem<T>::VEC, N = V / PER;
+    uint4 q[N];
+    __device__ __forceinline__ void load(const T* p) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) q[i] = *reinterpret_cast<const uint4*>(p + i * PER);
+    }
+    __device__ __forceinline__ void unpack(float* out) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const unsigned w[4] = {q[i].x, q[i].y, q[i].z, q[i].w};
+            if constexpr (PER == 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) out[i * 4 + j] = __uint_as_float(w[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    out[i * 8 + 2 * j] = __uint_as_float(w[j] << 16);
+                    out[i * 8 + 2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+                }
+            }
+        }
+    }
+};
+
 // Wide rows (more than two 16-byte chunks per lane of one wavefront): the whole workgroup
 // shares a row, so a thread keeps one chunk (MAXT of them beyond 256 chunks) instead of
 // four or eight, and the column sums of its chunks never leave its registers.  The row's
@@ -188,9 +214,35 @@ __global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __res
     }
     const int row0 = blockIdx.x * LNB_ROWS;
     const int nrow = min(LNB_ROWS, rows - row0);              // the same for every thread of the block
+    // The rows of a block follow each other (one barrier each), so the operands of the next
+    // row are requested, as raw 16-byte pieces, before the current row is worked on: their
+    // latency then overlaps the reductions, the barrier and the stores.
+    RawElems<T, V> n_dy[MAXT];
+    RawElems<TX, V> n_x[MAXT];
+    RawElems<TR, V> n_res[MAXT];
+    float n_mu = 0.f, n_rs = 0.f;
+    auto fetch = [&](int row) {
+        n_mu = mean[row]; n_rs = rstd[row];
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) {
+            const int c = tid + t * LNW_THREADS;
+            if (c < nchunk) {
+                n_dy[t].load(dy + (size_t)row * cols + c * V);
+                n_x[t].load(x + (size_t)row * cols + c * V);
+                if (res) n_res[t].load(res + (size_t)row * cols + c * V);
+            }
+        }
+    };
+    if (nrow > 0) fetch(row0);
     for (int rr = 0; rr < nrow; ++rr) {
         const int row = row0 + rr;
-        const float mu = mean[row], rs = rstd[row];
+        const float mu = n_mu, rs = n_rs;
+        RawElems<T, V> c_dy[MAXT];
+        RawElems<TX, V> c_x[MAXT];
+        RawElems<TR, V> c_res[MAXT];
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) { c_dy[t] = n_dy[t]; c_x[t] = n_x[t]; c_res[t] = n_res[t]; }
+        if (rr + 1 < nrow) fetch(row + 1);
         float dxh[MAXT][V], xh[MAXT][V];
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -198,8 +250,8 @@ __global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __res
             const int c = tid + t * LNW_THREADS;
             if (c < nchunk) {
                 float d[V], xv[V];
-                load_vec<T>(dy + (size_t)row * cols + c * V, d);
-                load_elems<TX, V>(x + (size_t)row * cols + c * V, xv);
+                c_dy[t].unpack(d);
+                c_x[t].unpack(xv);
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     xh[t][e] = (xv[e] - mu) * rs;
@@ -225,7 +277,7 @@ __global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __res
             const int c = tid + t * LNW_THREADS;
             if (c < nchunk) {
                 float rv[V], o[V];
-                if (res) load_elems<TR, V>(res + (size_t)row * cols + c * V, rv);       // no residual path: dx = LN'(dy)
+                if (res) c_res[t].unpack(rv);                                            // no residual path: dx = LN'(dy)
                 else
 #pragma unroll
                     for (int e = 0; e < V; ++e) rv[e] = 0.f;
