@@ -150,7 +150,7 @@ __device__ __forceinline__ void store8(float* p, const float* v) { store_vec<flo
 template <int EPI, bool RF32, bool CF32, int TM, int TN>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* slab, int row_base, int col_base, int m,
                                          int n, const bf16_t* __restrict__ bias, const bf16_t* __restrict__ R,
-                                         void* __restrict__ c, bf16_t* __restrict__ C2, int erf_form, int lane) {
+                                         void* __restrict__ c, bf16_t* __restrict__ C2, int epi_flag, int lane) {
     constexpr int WN = EpiSlab<TN>::WN, STRIDE = EpiSlab<TN>::STRIDE;
     constexpr int CPR = WN / 8;                // 8-column pieces per row
     constexpr int RPP = 64 / CPR;              // rows covered by the 64 lanes at once
@@ -191,7 +191,7 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
             } else if constexpr (EPI == EPI_BIAS_GELU) {
                 float g[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) { v[e] += bv[e]; g[e] = gelu_f(v[e], erf_form); }
+                for (int e = 0; e < 8; ++e) { v[e] += bv[e]; g[e] = gelu_f(v[e], epi_flag); }
                 store8(C + idx, v);
                 store8(C2 + idx, g);
             } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
@@ -204,10 +204,10 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
                 float u[8];
                 load8(R + idx, u);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], erf_form);
+                for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], epi_flag);
                 store8(C + idx, v);
             } else {
-                if (!erf_form) {               // for this epilogue the flag means: overwrite instead of accumulate
+                if (!epi_flag) {               // accumulate; with the flag set the result replaces C
                     float old[8];
                     load8(Cf + idx, old);
 #pragma unroll
@@ -224,7 +224,7 @@ template <int BM, int BN, int WGM, int WGN, int PF, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n, int splits, float* __restrict__ slabs,
+    int ldb, int epi, int epi_flag, int res_types, int tiles_m, int tiles_n, int splits, float* __restrict__ slabs,
     unsigned* __restrict__ arrivals) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;    // wavefront tile
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(
     static_assert(sizeof(lds) >= (size_t)WGM * WGN * EpiSlab<TN>::FLOATS * sizeof(float), "LDS too small for the epilogue");
     __syncthreads();
     float* slab = reinterpret_cast<float*>(lds) + (size_t)(tid >> 6) * EpiSlab<TN>::FLOATS;
-#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, slab, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
+#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF, TM, TN>(acc, slab, rb0, cb0, m, n, bias, R, C, C2, epi_flag, lane)
     switch (epi) {
         case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
         case EPI_BIAS: CHIMERA_EPI(EPI_BIAS, false, false); break;
@@ -394,7 +394,7 @@ template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_K
 __device__ __forceinline__ void gemm_async_tile(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n, int block_id,
+    int ldb, int epi, int epi_flag, int res_types, int tiles_m, int tiles_n, int block_id,
     float* __restrict__ bsum = nullptr, bool xcd_remap = true) {
     constexpr int NT = WGM * WGN * WGK * 64;
     constexpr int KSUB = BK / 16 / WGK;                                   // 16-wide k slices per wavefront and step
@@ -519,7 +519,7 @@ __device__ __forceinline__ void gemm_async_tile(
     __syncthreads();
     float* slab = reinterpret_cast<float*>(lds) + (size_t)(tid >> 6) * EpiSlab<TN>::FLOATS;
     auto finish = [&](const auto& out, int rb0) {
-#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF>(out, slab, rb0, cb0, m, n, bias, R, C, C2, erf_form, lane)
+#define CHIMERA_EPI(E, RF, CF) epilogue<E, RF, CF>(out, slab, rb0, cb0, m, n, bias, R, C, C2, epi_flag, lane)
         if constexpr (ONLY_EPI == EPI_ACCUM_F32) { CHIMERA_EPI(EPI_ACCUM_F32, false, false); return; }
         switch (epi) {
             case EPI_NONE: CHIMERA_EPI(EPI_NONE, false, false); break;
@@ -542,7 +542,7 @@ __device__ __forceinline__ void gemm_async_tile(
 #pragma unroll
             for (int b = 0; b < TN; ++b) {
                 const int col = cb0 + b * 32 + lane;
-                if (col < n) bsum[col] = erf_form ? v[b] : bsum[col] + v[b];
+                if (col < n) bsum[col] = epi_flag ? v[b] : bsum[col] + v[b];
             }
     };
     if constexpr (WGK == 1) {
@@ -613,8 +613,8 @@ template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_K
 __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int erf_form, int res_types, int tiles_m, int tiles_n) {
-    gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, -1>(A, B, bias, R, C, C2, m, n, k, lda, ldb, epi, erf_form,
+    int ldb, int epi, int epi_flag, int res_types, int tiles_m, int tiles_n) {
+    gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, -1>(A, B, bias, R, C, C2, m, n, k, lda, ldb, epi, epi_flag,
                                                                 res_types, tiles_m, tiles_n, (int)blockIdx.x);
 }
 
@@ -652,8 +652,9 @@ __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_group_ker
 
 struct TileChoice { int bm, bn, splits; };
 
-// The kernels' `erf_form` argument: GeLU form for the GeLU epilogues; for the float-accumulate
-// epilogue it means "overwrite", which a single product never asks for.
+// The kernels' `epi_flag` argument modifies the epilogue: for the GeLU epilogues 1 selects the
+// erf form (0: tanh form); for the float-accumulate epilogue 1 makes the result replace C (and
+// the column sums replace bsum) instead of being added, which a single product never asks for.
 inline int epilogue_flag(const GemmArgs& g) { return g.epilogue == EPI_ACCUM_F32 ? 0 : g.gelu_erf; }
 
 TileChoice forced_tile() {
