@@ -371,6 +371,38 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     }
 }
 
+// The same for `gridDim.y` partial blocks at once (the LayerNorm backward passes of a whole
+// stage): block row y reduces partial + y * part_stride, laid out [nparts][dgamma | dbeta], into
+// the gradients of LayerNorm y = 2 * layer + (0: first, 1: second LayerNorm of the block).
+__global__ __launch_bounds__(256) void reduce_partials_batched_kernel(const float* __restrict__ partial, size_t part_stride,
+                                                                      int nparts, int cols, float* __restrict__ grads,
+                                                                      size_t layer_stride, LnGradOffsets off, int overwrite) {
+    __shared__ float red[8][32];
+    const int c = threadIdx.x & 31, q = threadIdx.x >> 5, n = 2 * cols;
+    const int i = blockIdx.x * 32 + c, y = blockIdx.y;
+    const float* part = partial + (size_t)y * part_stride;
+    float s = 0.f;
+    if (i < n) {
+        int p = q;
+        for (; p + 24 < nparts; p += 32) {
+            const float a0 = part[(size_t)p * n + i], a1 = part[(size_t)(p + 8) * n + i];
+            const float a2 = part[(size_t)(p + 16) * n + i], a3 = part[(size_t)(p + 24) * n + i];
+            s += (a0 + a1) + (a2 + a3);
+        }
+        for (; p < nparts; p += 8) s += part[(size_t)p * n + i];
+    }
+    red[q][c] = s;
+    __syncthreads();
+    if (q == 0 && i < n) {
+        float t = red[0][c];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) t += red[k][c];
+        float* g = grads + (size_t)(y >> 1) * layer_stride;
+        float* dst = i < cols ? g + off.gamma[y & 1] + i : g + off.beta[y & 1] + (i - cols);
+        *dst = overwrite ? t : *dst + t;
+    }
+}
+
 __global__ void fill_zero_kernel(float4* __restrict__ p, size_t n4, float* __restrict__ tail, int ntail) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -420,6 +452,7 @@ int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float
 #undef LN_BWD_CASE
 #undef LN_BWD_WIDE
     CHIMERA_LAUNCH_CHECK("layernorm backward");
+    if (!dgamma) return CHIMERA_OK;            // the caller reduces the partial sums later (layernorm_bwd_reduce)
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * cols + 31) / 32), dim3(256), 0, s, scratch, nblk, 2 * cols,
                        dgamma, dbeta, cols, overwrite);
     CHIMERA_LAUNCH_CHECK("layernorm backward reduce");
@@ -472,6 +505,17 @@ int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, 
     if (x_f32) return res_f32 ? ln_bwd_launch<float, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<float, bf16_t, bf16_t>(LN_BWD_ARGS);
     return res_f32 ? ln_bwd_launch<bf16_t, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<bf16_t, bf16_t, bf16_t>(LN_BWD_ARGS);
 #undef LN_BWD_ARGS
+}
+
+int layernorm_bwd_reduce(int rows, int cols, int count, const float* partial, size_t part_stride, float* grads,
+                         size_t layer_stride, const LnGradOffsets& off, int overwrite, void* stream) {
+    if (count < 1) return CHIMERA_OK;
+    if (rows < 1 || cols < 1 || !partial || !grads || count > 65535) return fail(CHIMERA_EINVAL, "layernorm backward reduce: bad arguments");
+    const int nblk = (rows + LNB_ROWS - 1) / LNB_ROWS;
+    hipLaunchKernelGGL(reduce_partials_batched_kernel, dim3((2 * cols + 31) / 32, count), dim3(256), 0, (hipStream_t)stream,
+                       partial, part_stride, nblk, cols, grads, layer_stride, off, overwrite);
+    CHIMERA_LAUNCH_CHECK("layernorm backward reduce (batched)");
+    return CHIMERA_OK;
 }
 
 size_t colsum_scratch_floats(int rows, int cols) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * cols; }

@@ -88,7 +88,7 @@ struct chimera_stage {
     size_t layer_stash, slot_bytes;
 
     // workspace layout (bytes)
-    size_t w_dy[2], w_dyf[2], w_dx1f, w_du[2], w_dh, w_dx1[2], w_dctx, w_dqkv[2], w_delta, w_scratch, w_scratch2, ws_bytes;
+    size_t w_dy[2], w_dyf[2], w_dx1f, w_du[2], w_dh, w_dx1[2], w_dctx, w_dqkv[2], w_delta, w_scratch, w_scratch2, w_lnpart, lnpart_floats, ws_bytes;
 
     const char* weights = nullptr;
     float* grads = nullptr;
@@ -165,6 +165,9 @@ void layout(chimera_stage* st) {
     const size_t sc = std::max(colsum_scratch_floats((int)M, (int)(4 * H)), layernorm_bwd_scratch_floats((int)M, (int)H));
     st->w_scratch = takeb(sc * 4);
     st->w_scratch2 = takeb(sc * 4);
+    // partial sums of every LayerNorm backward of a stage pass, reduced by one launch at its end
+    st->lnpart_floats = layernorm_bwd_scratch_floats((int)M, (int)H);
+    st->w_lnpart = takeb(st->lnpart_floats * 4 * 2 * st->L);
     st->ws_bytes = b;
 }
 
@@ -336,7 +339,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
         if (wgrad_group_ok(st, probe)) { fresh = 1; st->grads_pending_zero = false; }
         else TRY(flush_pending_zero(st));
     }
-    float* scratch = (float*)(st->ws + st->w_scratch);
+    float* lnpart = (float*)(st->ws + st->w_lnpart);
     float* scratch2 = (float*)(st->ws + (st->have_side ? st->w_scratch2 : st->w_scratch));
     hipStream_t gs = st->have_side ? st->side : st->stream;       // stream of the parameter gradients
     void* dh = st->ws + st->w_dh;
@@ -393,7 +396,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
         }
         TRY(linear_dgrad(st, M, 4 * H, H, du, st->W(l, st->o_w_fc1), nullptr, dh, EPI_NONE));
         TRY(st_ln_bwd(st, dh, x1, wide, mean2, rstd2,
-                      st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, st->G(l, st->o_ln2_g), st->G(l, st->o_ln2_b), scratch, fresh));
+                      st->W(l, st->o_ln2_g), dyr, dyr_f32, dx1, dx1f, nullptr, nullptr, lnpart + (size_t)(2 * l + 1) * st->lnpart_floats, fresh));
         // x1 = x + ctx Wo + bo
         if (!grouped) {
             TRY(fork_to_side(st, 2));
@@ -422,10 +425,16 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
         if (st->have_side && l + 1 <= L - 1) HIP_TRY(hipStreamWaitEvent(st->stream, st->ev_side[(l + 1) & 1], 0));
         TRY(st_ln_bwd(st, dh, x, x_f32, mean1, rstd1,
                       st->W(l, st->o_ln1_g), wide ? (const void*)dx1f : (const void*)dx1, wide, dx, dxf,
-                      st->G(l, st->o_ln1_g), st->G(l, st->o_ln1_b), scratch, fresh));
+                      nullptr, nullptr, lnpart + (size_t)(2 * l) * st->lnpart_floats, fresh));
         dy = dx;
         dyr = dxf ? (const void*)dxf : (const void*)dx;
         dyr_f32 = dxf != nullptr;
+    }
+    // dgamma, dbeta of all 2L LayerNorms from their partial sums, in one launch
+    {
+        const LnGradOffsets off{{st->o_ln1_g, st->o_ln2_g}, {st->o_ln1_b, st->o_ln2_b}};
+        ProfScope prof(PC_LN_BWD, 0.0, st->stream);
+        TRY(layernorm_bwd_reduce(M, H, 2 * L, lnpart, st->lnpart_floats, st->grads, st->layer_params, off, fresh, st->stream));
     }
     // the stash slot, the workspace and the gradient buffers are free for the next op only
     // once the side stream has drained
