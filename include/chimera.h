@@ -310,6 +310,10 @@ int chimera_worker_set_timing(int on);
 /* Milliseconds the last chimera_run_worker* spent in forward ops and in
  * backward ops (HIP events around every op), and the op counts. */
 int chimera_worker_last_timing(double* h_fwd_ms, double* h_bwd_ms, int* h_nf, int* h_nb);
+/* Host milliseconds the last chimera_run_worker* needed to build the schedule and enqueue
+ * every launch, i.e. up to (not including) its wait for the streams: the replay is bound by
+ * the host once this approaches the iteration time. */
+int chimera_worker_last_enqueue_ms(double* h_ms);
 
 /* Per-kernel-class timing of everything the stages launch while enabled: a HIP
  * event pair brackets every launch (this slows the replay a little, so keep it

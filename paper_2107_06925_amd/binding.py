@@ -68,6 +68,7 @@ _SIGNATURES = {
     "chimera_profile_reset": (_i, []),
     "chimera_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "chimera_model_select": (_i, [_i, _i, C.c_int64, C.c_double, C.c_double, C.c_double, _i, _i, _p, _p, _p]),
+    "chimera_worker_last_enqueue_ms": (_i, [_p]),
     "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
     "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p, _i, _p]),
@@ -314,6 +315,12 @@ def chimera_worker_last_timing():
     f, b, nf, nb = C.c_double(), C.c_double(), C.c_int(), C.c_int()
     check(lib().chimera_worker_last_timing(C.byref(f), C.byref(b), C.byref(nf), C.byref(nb)))
     return dict(fwd_ms=f.value, bwd_ms=b.value, n_fwd=nf.value, n_bwd=nb.value)
+
+
+def chimera_worker_last_enqueue_ms():
+    v = C.c_double()
+    check(lib().chimera_worker_last_enqueue_ms(C.byref(v)))
+    return v.value
 
 
 PROFILE_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum")

@@ -2,6 +2,7 @@
 // with in-place float gradient accumulation), its activation stash, and the
 // replay of a worker's op list (section 3.1: worker i runs stage i of the down
 // pipeline and stage D-1-i of the up pipeline in the merged 1F1B order).
+#include <chrono>
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -451,6 +452,7 @@ struct Worker {
     int timing = 0;
     double fwd_ms = 0, bwd_ms = 0;
     int nf = 0, nb = 0;
+    double enqueue_ms = 0;                    // host time of the last replay up to its final wait
 } g_worker;
 
 }  // namespace
@@ -678,6 +680,7 @@ int chimera_worker_set_timing(int on) { g_worker.timing = on ? 1 : 0; return CHI
 int chimera_run_worker_pipes(int algo, int rank, int D, int N, int f) {
     Worker& wk = g_worker;
     if (wk.pipes.empty() || !wk.pipes[0]) return fail(CHIMERA_ESTATE, "no worker bound");
+    const auto t_start = std::chrono::steady_clock::now();
     std::vector<std::vector<Op>> lists;
     TRY(build_schedule(algo, D, N, f, lists));
     if (rank < 0 || rank >= D) return fail(CHIMERA_EINVAL, "rank %d outside [0,%d)", rank, D);
@@ -735,6 +738,7 @@ int chimera_run_worker_pipes(int algo, int rank, int D, int N, int f) {
         }
         if (wk.timing) (void)hipEventRecord(ev[2 * i + 1], st->stream);
     }
+    wk.enqueue_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count();
     // one wait per distinct stream
     hipError_t e = hipSuccess;
     std::vector<hipStream_t> waited;
@@ -771,6 +775,12 @@ int chimera_worker_last_timing(double* h_fwd_ms, double* h_bwd_ms, int* h_nf, in
     if (h_bwd_ms) *h_bwd_ms = g_worker.bwd_ms;
     if (h_nf) *h_nf = g_worker.nf;
     if (h_nb) *h_nb = g_worker.nb;
+    return CHIMERA_OK;
+}
+
+int chimera_worker_last_enqueue_ms(double* h_ms) {
+    if (!h_ms) return fail(CHIMERA_EINVAL, "h_ms is NULL");
+    *h_ms = g_worker.enqueue_ms;
     return CHIMERA_OK;
 }
 
