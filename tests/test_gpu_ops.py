@@ -253,7 +253,8 @@ def test_colsum(dtype, rows, cols):
     assert_close(to_np(out) - 3.0, x.astype(np.float64).sum(0), b.F32, "colsum", scale=10.0)
 
 
-ATTN_SHAPES = [(2, 64, 4, 32), (1, 100, 2, 64), (2, 256, 3, 64), (1, 192, 2, 128), (3, 1, 2, 64), (1, 77, 1, 16)]
+ATTN_SHAPES = [(2, 64, 4, 32), (1, 100, 2, 64), (2, 256, 3, 64), (1, 192, 2, 128), (3, 1, 2, 64), (1, 77, 1, 16),
+               (8, 200, 32, 64), (2, 333, 2, 128)]        # many (sequence, head) pairs; a ragged last tile at head dim 128
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
