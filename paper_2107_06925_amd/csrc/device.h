@@ -75,24 +75,27 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
-// tanh(x) = 1 - 2 / (1 + exp(2x)), on the hardware exp2 and reciprocal; absolute error below
-// 1e-6, exact limits for large |x| (exp overflows to inf -> 1, underflows to 0 -> -1).
-__device__ __forceinline__ float fast_tanh(float x) {
-    const float e = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);      // exp(2x)
-    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
+// GeLU, tanh form: 0.5 u (1 + tanh z), z = sqrt(2/pi) (u + 0.044715 u^3); erf form: u Phi(u).
+// 0.5 (1 + tanh z) is the logistic function of 2z, which needs one hardware exp2 and one
+// reciprocal: s = 1 / (1 + exp(-2z)).  Large |z| saturate exactly (exp2 -> inf gives s = 0,
+// exp2 -> 0 gives s = 1).
+__device__ __forceinline__ float gelu_logistic(float u) {
+    const float u2 = u * u;
+    const float m2z = u * __builtin_fmaf(u2, -2.0f * 0.79788456080286536f * 0.044715f * 1.4426950408889634f,
+                                         -2.0f * 0.79788456080286536f * 1.4426950408889634f);    // -2 z log2(e)
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(m2z));
 }
-
-// GeLU, tanh form: 0.5 u (1 + tanh(sqrt(2/pi) (u + 0.044715 u^3))); erf form: u Phi(u).
 __device__ __forceinline__ float gelu_f(float u, int erf_form) {
     if (erf_form) return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f));
-    const float t = fast_tanh(0.79788456080286536f * (u + 0.044715f * u * u * u));
-    return 0.5f * u * (1.0f + t);
+    return u * gelu_logistic(u);
 }
+// d/du [u s(2z)] = s + u s (1 - s) 2 z'(u),  z'(u) = sqrt(2/pi) (1 + 3 * 0.044715 u^2)
 __device__ __forceinline__ float gelu_grad_f(float u, int erf_form) {
     if (erf_form)
         return 0.5f * (1.0f + erff(u * 0.70710678118654752f)) + u * __expf(-0.5f * u * u) * 0.39894228040143268f;
-    const float t = fast_tanh(0.79788456080286536f * (u + 0.044715f * u * u * u));
-    return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * 0.79788456080286536f * (1.0f + 3.0f * 0.044715f * u * u);
+    const float s = gelu_logistic(u);
+    const float dz2 = __builtin_fmaf(u * u, 2.0f * 0.79788456080286536f * 3.0f * 0.044715f, 2.0f * 0.79788456080286536f);
+    return __builtin_fmaf(u * dz2, s - s * s, s);
 }
 
 // Global -> LDS without passing through registers: lane i of the wavefront writes the 16
