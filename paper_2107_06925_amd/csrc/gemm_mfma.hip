@@ -191,7 +191,14 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
             } else if constexpr (EPI == EPI_BIAS_GELU) {
                 float g[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) { v[e] += bv[e]; g[e] = gelu_f(v[e], epi_flag); }
+                for (int e = 0; e < 8; ++e) v[e] += bv[e];
+                if (epi_flag) {                               // one wavefront-uniform branch per piece, not per element
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) g[e] = gelu_f(v[e], 1);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) g[e] = gelu_f(v[e], 0);
+                }
                 store8(C + idx, v);
                 store8(C2 + idx, g);
             } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
@@ -203,8 +210,13 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
             } else if constexpr (EPI == EPI_DGELU) {
                 float u[8];
                 load8(R + idx, u);
+                if (epi_flag) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], epi_flag);
+                    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], 1);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], 0);
+                }
                 store8(C + idx, v);
             } else {
                 if (!epi_flag) {               // accumulate; with the flag set the result replaces C
