@@ -25,6 +25,8 @@
 // is loaded straight from global memory into MFMA operand registers.
 #include "device.h"
 
+#include <type_traits>
+
 namespace chimera {
 
 namespace {
@@ -164,8 +166,11 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
         for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
     float m = NEG_BIG, lsum = 0.f;
 
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1, k0 = t * 64;
+    // one step of the key loop; the LDS buffer index is a compile-time constant so that every LDS
+    // address is the lane's base plus an immediate
+    auto step = [&](int t, auto buf_c) {
+        constexpr int buf = decltype(buf_c)::value;
+        const int k0 = t * 64;
         wait_vmcnt<0>();                   // this wavefront's share of tile t has landed
         __syncthreads();                   // everyone's has; and tile t-1 is consumed, so its buffer is free
         if (t + 1 < ntiles) {
@@ -233,6 +238,10 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
                     o[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_ut<D>(Vs[buf], t2 * 32, J, lane), pf, o[t2], 0, 0, 0);
             }
         }
+    };
+    for (int t = 0; t < ntiles; t += 2) {
+        step(t, std::integral_constant<int, 0>{});
+        if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
     }
 
     if (qrow < S) {
@@ -307,8 +316,9 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restri
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dk[t][r] = 0.f; dv[t][r] = 0.f; }
 
-    for (int t = qt0; t < ntiles; ++t) {
-        const int i0 = t * 64, buf = (t - qt0) & 1;
+    auto step = [&](int t, auto buf_c) {        // LDS buffer index at compile time: addresses become base + immediate
+        constexpr int buf = decltype(buf_c)::value;
+        const int i0 = t * 64;
         wait_vmcnt<0>();                   // this wavefront's share of tile t (and its statistics) has arrived
         if (tid < 64) lse2[buf][tid] = stat;
         else if (tid < 128) dl[buf][tid - 64] = stat;
@@ -364,6 +374,10 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restri
                 }
             }
         }
+    };
+    for (int t = qt0; t < ntiles; t += 2) {
+        step(t, std::integral_constant<int, 0>{});
+        if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
     }
     if (jrow < S) {
         bf16_t* out = dqkv + ((size_t)b * S + jrow) * ld + h * D;
@@ -439,8 +453,9 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restric
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[t][r] = 0.f;
 
-    for (int t = 0; t < ntiles; ++t) {
-        const int k0 = t * 64, buf = t & 1;
+    auto step = [&](int t, auto buf_c) {        // LDS buffer index at compile time
+        constexpr int buf = decltype(buf_c)::value;
+        const int k0 = t * 64;
         wait_vmcnt<0>();
         __syncthreads();
         if (t + 1 < ntiles) fetch(t + 1, buf ^ 1);
@@ -479,6 +494,10 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restric
                 }
             }
         }
+    };
+    for (int t = 0; t < ntiles; t += 2) {
+        step(t, std::integral_constant<int, 0>{});
+        if (t + 1 < ntiles) step(t + 1, std::integral_constant<int, 1>{});
     }
     if (qrow < S) {
         bf16_t* out = dqkv + ((size_t)b * S + qrow) * ld + h * D;
