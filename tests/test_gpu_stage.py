@@ -122,6 +122,14 @@ def test_worker_bf16_small_and_deterministic():
         assert np.array_equal(st.read_grads(), ref)
     for g in range(cfg.N):
         assert torch.equal(outs[g][0], y_first[g])
+    # the host time of the replay up to its final wait is reported, and is below the whole call's
+    import time
+    for st in stages:
+        st.zero_grads()
+    t0 = time.perf_counter()
+    b.chimera_run_worker(1, cfg.D, cfg.N)
+    whole_ms = (time.perf_counter() - t0) * 1e3
+    assert 0.0 < b.chimera_worker_last_enqueue_ms() <= whole_ms
 
 
 @pytest.mark.parametrize("algo", [b.GPIPE, b.ONE_F_ONE_B])
