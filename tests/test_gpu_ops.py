@@ -112,6 +112,7 @@ GROUPS = [
     (1024, [(256, 1024), (1024, 256), (256, 256), (256, 768)]),     # 48 tiles: the k-sliced 8-wavefront variant
     (128, [(1024, 4096), (4096, 1024), (1024, 1024), (1024, 3072)]),   # 768 tiles: the two-workgroups-per-CU variant
     (64, [(2048, 4096), (4096, 2056), (2048, 2048)]),                  # enough 256x256 tiles for the whole chip, ragged edge
+    (64, [(1024, 3080), (1024, 1032), (1032, 4096), (2056, 1024)]),    # 188 tiles of 256x256: fewer than CUs, not a multiple of 8
 ]
 
 
