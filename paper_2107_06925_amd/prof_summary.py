@@ -19,7 +19,7 @@ def short(name):
         args = re.findall(r"L[ib](\d+)E", m.group(2))
         types = "".join("f" if t == "f" else "b" for t in re.findall(r"(?<![A-Za-z])(f|DF16b)(?=[A-Z_]|$)", m.group(2).split("L")[0]))
         return "%s<%s%s>" % (m.group(1), (types + ";") if types else "", ",".join(args))
-    return name.split("(")[0][:70]
+    return name.replace("bool _Accum", "bf16").split("(")[0][:70]        # some demanglers print __bf16 that way
 
 
 def stats(path):
