@@ -662,6 +662,26 @@ __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_group_ker
         EPI_ACCUM_F32, grp.overwrite, 0, grp.tiles_m[p], grp.tiles_n[p], gid - grp.first[p], grp.bsum[p], false);
 }
 
+// A launch of 256x256 tiles runs in rounds of NUM_CUS tiles, and a last round with few tiles
+// costs as much as a full one.  The products here can be cut along m without touching the data
+// (row bands of A and C are just pointer offsets), so the last `b` bands of 256 rows may go to a
+// second launch with 128x128 tiles instead.  Cost estimate in units of one 256x256 round: a round
+// of 128x128 tiles (quarter of the flops, 1.6x the time per flop) counts 0.45.  Returns the b
+// that minimises it (0: leave the product whole); `other` = 256x256 tiles of the launch that do
+// not belong to this product.
+int bands_to_peel(long other, int tm, int tn, int n) {
+    const int tn128 = (n + 127) / 128;
+    auto rounds = [](long tiles) { return (double)((tiles + NUM_CUS - 1) / NUM_CUS); };
+    const double whole = rounds(other + (long)tm * tn);
+    int best_b = 0;
+    double best = whole - 0.25;                                  // a split must pay for its second launch
+    for (int b = 1; b < tm; ++b) {
+        const double est = rounds(other + (long)(tm - b) * tn) + 0.45 * rounds((long)b * 2 * tn128);
+        if (est < best) { best = est; best_b = b; }
+    }
+    return best_b;
+}
+
 struct TileChoice { int bm, bn, splits; };
 
 // The kernels' `epi_flag` argument modifies the epilogue: for the GeLU epilogues 1 selects the
@@ -784,7 +804,27 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");                 // tuning aid: 0 = register-staged kernels
     const bool can_async = g.k % BK == 0 && g.m >= 8 && g.n >= 8 && t.splits == 1 && !(mode && mode[0] == '0');
     if (can_async) {
-        if (t.bm == 256 && t.bn == 256) return launch_async<256, 256, 2, 4, 1, 2>(g, s);
+        if (t.bm == 256 && t.bn == 256) {
+            const int tm = (g.m + 255) / 256, tn = (g.n + 255) / 256;
+            const int b = forced_tile().bm ? 0 : bands_to_peel(0, tm, tn, g.n);
+            if (b > 0 && g.m - (tm - b) * 256 >= 8) {
+                // rows [0, m0) with 256x256 tiles, rows [m0, m) with 128x128 tiles
+                const size_t m0 = (size_t)(tm - b) * 256;
+                const size_t csz = (g.epilogue == EPI_ACCUM_F32 || g.c_f32) ? 4 : 2;
+                GemmArgs head = g, tail = g;
+                head.m = (int)m0;
+                tail.m = g.m - (int)m0;
+                tail.a = (const char*)g.a + (g.a_kc ? m0 * g.lda : m0) * 2;
+                tail.c = (char*)g.c + m0 * g.n * csz;
+                if (g.c2) tail.c2 = (char*)g.c2 + m0 * g.n * 2;
+                if (g.r) tail.r = (const char*)g.r + m0 * g.n * (g.r_f32 ? 4 : 2);
+                if (int rc = launch_async<256, 256, 2, 4, 1, 2>(head, s)) return rc;
+                const long t128 = (long)((tail.m + 127) / 128) * ((tail.n + 127) / 128);
+                if (t128 < 2 * NUM_CUS) return launch_async<128, 128, 2, 2, 2, 3>(tail, s);
+                return launch_async<128, 128, 2, 2, 1, 2>(tail, s);
+            }
+            return launch_async<256, 256, 2, 4, 1, 2>(g, s);
+        }
         if (t.bm == 128 && t.bn == 128) {
             const long t128 = (long)((g.m + 127) / 128) * ((g.n + 127) / 128);
             const bool ksplit = mode ? !std::strcmp(mode, "4k") : t128 < 2 * NUM_CUS;
@@ -807,19 +847,8 @@ bool gemm_mfma_group_supports(int count, const GemmArgs* g) {
     return true;
 }
 
-int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream) {
-    if (!gemm_mfma_group_supports(count, g))
-        return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
-                    "one contraction length (a multiple of %d)", GROUP_MAX, BK);
-    // tile choice as for single products: 256x256 once such tiles occupy most of the chip, else
-    // 128x128.  (192 tiles of 256x256 on 256 CUs beat 768 tiles of 128x128: they pull half the
-    // bytes from L2 into LDS, which is what limits these kernels, and the CUs they leave free
-    // serve the launches of the other stream.)
-    long t256 = 0;
-    for (int i = 0; i < count; ++i) t256 += (long)((g[i].m + 255) / 256) * ((g[i].n + 255) / 256);
-    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");
-    const TileChoice forced = forced_tile();
-    const int tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= 160 ? 256 : 128);
+namespace {
+int launch_group_tiled(int count, const GemmArgs* g, float* const* bsum, int overwrite, int tile, hipStream_t stream) {
     GemmGroup grp{};
     grp.count = count; grp.k = g[0].k; grp.overwrite = overwrite ? 1 : 0;
     int tiles = 0;
@@ -832,11 +861,50 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int o
         tiles += grp.tiles_m[i] * grp.tiles_n[i];
     }
     for (int i = count; i <= GROUP_MAX; ++i) grp.first[i] = tiles;
-    if (tile == 256) return launch_group<256, 256, 2, 4, 1, 2>(grp, (hipStream_t)stream);
+    if (tile == 256) return launch_group<256, 256, 2, 4, 1, 2>(grp, stream);
     // two workgroups per CU or the k-sliced 8-wavefront form
+    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");
     const bool ksplit = mode ? !std::strcmp(mode, "4k") : tiles < 2 * NUM_CUS;
-    if (ksplit) return launch_group<128, 128, 2, 2, 2, 3>(grp, (hipStream_t)stream);
-    return launch_group<128, 128, 2, 2, 1, 2>(grp, (hipStream_t)stream);
+    if (ksplit) return launch_group<128, 128, 2, 2, 2, 3>(grp, stream);
+    return launch_group<128, 128, 2, 2, 1, 2>(grp, stream);
+}
+}  // namespace
+
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream) {
+    if (!gemm_mfma_group_supports(count, g))
+        return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
+                    "one contraction length (a multiple of %d)", GROUP_MAX, BK);
+    // tile choice as for single products: 256x256 once such tiles occupy most of the chip, else
+    // 128x128.  (192 tiles of 256x256 on 256 CUs beat 768 tiles of 128x128: they pull half the
+    // bytes from L2 into LDS, which is what limits these kernels, and the CUs they leave free
+    // serve the launches of the other stream.)
+    long t256 = 0;
+    for (int i = 0; i < count; ++i) t256 += (long)((g[i].m + 255) / 256) * ((g[i].n + 255) / 256);
+    const TileChoice forced = forced_tile();
+    const int tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= 160 ? 256 : 128);
+    hipStream_t s = (hipStream_t)stream;
+    if (tile != 256 || forced.bm) return launch_group_tiled(count, g, bsum, overwrite, tile, s);
+    // a nearly empty last round: the last row bands of one product go to a 128x128 launch
+    int best_p = -1, best_b = 0;
+    double best_rounds = 1e30;
+    for (int p = 0; p < count; ++p) {
+        const int tm = (g[p].m + 255) / 256, tn = (g[p].n + 255) / 256;
+        const int b = bands_to_peel(t256 - (long)tm * tn, tm, tn, g[p].n);
+        if (!b || g[p].m - (tm - b) * 256 < 8) continue;
+        const double est = (double)((t256 - (long)b * tn + NUM_CUS - 1) / NUM_CUS) + 0.45 * (double)(((long)b * 2 * ((g[p].n + 127) / 128) + NUM_CUS - 1) / NUM_CUS);
+        if (est < best_rounds) { best_rounds = est; best_p = p; best_b = b; }
+    }
+    if (best_p < 0) return launch_group_tiled(count, g, bsum, overwrite, 256, s);
+    GemmArgs head[GROUP_MAX];
+    for (int i = 0; i < count; ++i) head[i] = g[i];
+    const size_t m0 = (size_t)((g[best_p].m + 255) / 256 - best_b) * 256;
+    head[best_p].m = (int)m0;
+    GemmArgs tail = g[best_p];
+    tail.m = g[best_p].m - (int)m0;
+    tail.a = (const char*)tail.a + m0 * 2;                      // A is [k, m]: the band starts m0 columns in
+    tail.c = (char*)tail.c + m0 * tail.n * sizeof(float);
+    if (int rc = launch_group_tiled(count, head, bsum, overwrite, 256, s)) return rc;
+    return launch_group_tiled(1, &tail, nullptr, overwrite, 128, s);   // the column sums come from the first launch
 }
 
 }  // namespace chimera

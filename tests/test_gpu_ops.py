@@ -75,6 +75,35 @@ def test_gemm_epilogues(dtype, impl, gelu_erf):
     assert_close(to_np(c), acc * bo.gelu_grad(R.astype(np.float64), kind), dtype, "dgelu")
 
 
+def test_gemm_last_row_bands_on_small_tiles():
+    """272 tiles of 256x256 are one round of the 256 CUs plus 16 tiles: the last band of 256 rows
+    (here 200 of them exist) goes out as a second launch of 128x128 tiles.  Every epilogue has
+    to find its row-offset operands (residual, second output, float output) in that launch."""
+    import torch
+    m, n, k = 16 * 256 + 200, 4096, 64
+    A, B = _rand((m, k), 1, b.BF16), _rand((k, n), 2, b.BF16, 0.2)
+    bias, R = _rand((n,), 3, b.BF16), _rand((m, n), 4, b.BF16)
+    acc = A.astype(np.float64) @ B.astype(np.float64)
+    da, db, dbias, dr = to_dev(A, b.BF16), to_dev(B, b.BF16), to_dev(bias, b.BF16), to_dev(R, b.BF16)
+    c = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    c2 = torch.empty_like(c)
+    b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_BIAS_GELU, bias=dbias, c2=c2)
+    assert_close(to_np(c), acc + bias, b.BF16, "bias+gelu: u")
+    assert_close(to_np(c2), bo.gelu_fwd(acc + bias, "tanh"), b.BF16, "bias+gelu: g")
+    b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_BIAS_RESIDUAL, bias=dbias, r=dr)
+    assert_close(to_np(c), acc + bias + R, b.BF16, "bias+residual")
+    b.chimera_op_gemm(da, db, c, m, n, k, 1, 0, b.EPI_DGELU, r=dr)
+    assert_close(to_np(c), acc * bo.gelu_grad(R.astype(np.float64), "tanh"), b.BF16, "dgelu")
+    # dgrad layout (both operands k-contiguous) and the float-accumulating weight-gradient layout
+    dbt = to_dev(np.ascontiguousarray(B.T), b.BF16)
+    b.chimera_op_gemm(da, dbt, c, m, n, k, 1, 1, b.EPI_NONE)
+    assert_close(to_np(c), acc, b.BF16, "k-contiguous B")
+    dat = to_dev(np.ascontiguousarray(A.T), b.BF16)
+    dw = torch.ones((m, n), device="cuda")
+    b.chimera_op_gemm(dat, db, dw, m, n, k, 0, 0, b.EPI_ACCUM_F32)
+    assert_close(to_np(dw) - 1.0, acc, b.BF16, "index-contiguous A, float accumulate")
+
+
 def test_gemm_split_k_matches_unsplit_and_is_reproducible():
     """On request (tile override plus a workspace) the bf16 kernel splits k over several
     workgroups per tile; partial sums are added in a fixed order, so two runs agree bit
@@ -113,6 +142,7 @@ GROUPS = [
     (128, [(1024, 4096), (4096, 1024), (1024, 1024), (1024, 3072)]),   # 768 tiles: the two-workgroups-per-CU variant
     (64, [(2048, 4096), (4096, 2056), (2048, 2048)]),                  # enough 256x256 tiles for the whole chip, ragged edge
     (64, [(1024, 3080), (1024, 1032), (1032, 4096), (2056, 1024)]),    # 188 tiles of 256x256: fewer than CUs, not a multiple of 8
+    (64, [(2048, 2048), (2048, 2048), (2048, 2048), (2248, 2048)]),    # 264 tiles: the last 200 rows of one product go to a 128x128 launch
 ]
 
 
