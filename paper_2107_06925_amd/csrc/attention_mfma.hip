@@ -100,29 +100,31 @@ __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, WAVE)
 
 // ------------------------------------------------------------------- forward
 // Which 128-row tile (by rank: 0 = the one with the most work under the causal mask), head and
-// sequence a workgroup of the 1-D grid takes; false for the padding workgroups.  Without a mask
-// the tiles of one (sequence, head) pair follow each other.  With the causal mask a tile's work
-// grows with its position, so the longest tiles of ALL pairs are dispatched first (rank slowest);
-// the pair count is padded to a multiple of 8 so that a pair always lands on the same XCD
-// (workgroup ids go round-robin over the 8 XCDs) and its K and V stay in that XCD's L2.
+// sequence a workgroup of the 1-D grid takes; false for the padding workgroups.  Workgroup ids
+// go round-robin over the 8 XCDs, so the (sequence, head) pair is chosen by id mod 8 first (the
+// pair count is padded to a multiple of 8): all tiles of a pair then run on one XCD and its K, V
+// (or Q, dO) are fetched into one L2 instead of up to eight.  Without a mask a group of 8 pairs
+// works through its tiles before the next group starts.  With the causal mask a tile's work grows
+// with its position, so the longest tiles of ALL pairs are dispatched first (rank slowest).
 template <bool CAUSAL>
 __device__ __forceinline__ bool attn_tile_of(int S, int heads, int batch, int& rank, int& h, int& b) {
     const int T = (S + 127) / 128, bid = (int)blockIdx.x;
+    const int pairs = heads * batch, padded = (pairs + 7) & ~7;
+    int p;
     if constexpr (CAUSAL) {
-        const int pairs = heads * batch, padded = (pairs + 7) & ~7;
-        const int p = bid % padded;
+        p = bid % padded;
         rank = bid / padded;
-        h = p % heads; b = p / heads;
-        return p < pairs;
     } else {
-        rank = bid % T;
-        h = (bid / T) % heads; b = bid / (T * heads);
-        return true;
+        const int j = bid >> 3;
+        rank = j % T;
+        p = (j / T) * 8 + (bid & 7);
     }
+    h = p % heads; b = p / heads;
+    return p < pairs;
 }
 inline unsigned attn_grid(const AttnArgs& a) {
     const unsigned T = (a.seq + 127) / 128, pairs = (unsigned)a.heads * a.batch;
-    return a.causal ? T * ((pairs + 7) & ~7u) : T * pairs;
+    return T * ((pairs + 7) & ~7u);
 }
 
 // The forward moves its K and V tiles global -> LDS directly (lds_dma16), one tile ahead of
