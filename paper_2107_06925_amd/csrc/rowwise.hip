@@ -84,7 +84,7 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
                                                                 T* __restrict__ dx_lo, float* __restrict__ dx_hi,
                                                                 float* __restrict__ partial, int rows, int cols) {
     constexpr int V = Elem<T>::VEC;
-    extern __shared__ float red[];   // [2][cols]
+    extern __shared__ float red[];   // [LN_WAVES][2][cols]
     const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
     const int nchunk = cols / V;
     float ag[MAXT][V], ab[MAXT][V], g[MAXT][V];
@@ -139,26 +139,29 @@ __global__ __launch_bounds__(LN_WAVES* WAVE) void ln_bwd_kernel(const T* __restr
             }
         }
     }
-    // fixed-order combination over the wavefronts of the block
-    for (int w = 0; w < LN_WAVES; ++w) {
-        if (wave == w) {
+    // Fixed-order combination over the wavefronts of the block: every wavefront parks its sums
+    // in its own LDS rows (16-byte stores), one barrier, then each thread adds the LN_WAVES
+    // values of its columns in wavefront order and writes the block's partial row.
+    float* mine = red + (size_t)wave * 2 * cols;
 #pragma unroll
-            for (int t = 0; t < MAXT; ++t) {
-                const int c = lane + t * WAVE;
-                if (c < nchunk) {
-#pragma unroll
-                    for (int e = 0; e < V; ++e) {
-                        const int col = c * V + e;
-                        if (w == 0) { red[col] = ag[t][e]; red[cols + col] = ab[t][e]; }
-                        else { red[col] += ag[t][e]; red[cols + col] += ab[t][e]; }
-                    }
-                }
-            }
+    for (int t = 0; t < MAXT; ++t) {
+        const int c = lane + t * WAVE;
+        if (c < nchunk) {
+            store_elems<float, V>(mine + c * V, ag[t]);
+            store_elems<float, V>(mine + cols + c * V, ab[t]);
         }
-        __syncthreads();
     }
+    __syncthreads();
     float* out = partial + (size_t)blockIdx.x * 2 * cols;
-    for (int i = threadIdx.x; i < 2 * cols; i += LN_WAVES * WAVE) out[i] = red[i];
+    for (int i = threadIdx.x * 4; i < 2 * cols; i += LN_WAVES * WAVE * 4) {
+        float4 acc = *reinterpret_cast<const float4*>(red + i);
+#pragma unroll
+        for (int w = 1; w < LN_WAVES; ++w) {
+            const float4 v = *reinterpret_cast<const float4*>(red + (size_t)w * 2 * cols + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<float4*>(out + i) = acc;
+    }
 }
 
 // V consecutive elements of type T as they come from memory (16-byte pieces), widened later.
@@ -436,7 +439,7 @@ int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float
     const int per_lane = (cols / V + WAVE - 1) / WAVE;
     const int nblk = (rows + LNB_ROWS - 1) / LNB_ROWS;
     const dim3 grid(nblk), block(LN_WAVES * WAVE);
-    const size_t lds = (size_t)2 * cols * sizeof(float);
+    const size_t lds = (size_t)LN_WAVES * 2 * cols * sizeof(float);
 #define LN_BWD_CASE(N)                                                                                              \
     hipLaunchKernelGGL((ln_bwd_kernel<TX, TR, T, N>), grid, block, lds, s, (const T*)dy, (const TX*)x, mean, rstd,   \
                        (const T*)gamma, (const TR*)res, (T*)dx_lo, dx_hi, scratch, rows, cols)
