@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the grouped weight-gradient kernel, from two rocprofv3 --pmc runs of
 # this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the kernel's
 # launches), each scaled by what the same counter reads for a streaming kernel of known size
-# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (114915.1 * 2.00 + 49224.1) KiB.
+# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (114950.1 * 2.00 + 49215.9) KiB.
 
 
 def _group_kernel_params(hidden):
@@ -37,7 +37,7 @@ def _group_kernel_params(hidden):
     return "128,128,2,2,2,3" if sum(t(m, 128) * t(n, 128) for m, n in shapes) < 512 else "128,128,2,2,1,2"
 
 
-WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((114915.1 * 2.00 + 49224.1) * 1024)}
+WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((114950.1 * 2.00 + 49215.9) * 1024)}
 
 
 def _cpu_baseline(cfg, blocks=6):
