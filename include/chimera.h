@@ -341,12 +341,21 @@ int chimera_profile_read(int cls, double* h_ms, long long* h_launches, double* h
  * 5 C (float, always) += acc.  C, C2, R have leading dimension n.
  * EINVAL if k, n or a leading dimension is not a multiple of 8.
  * d_workspace (may be NULL): chimera_op_gemm_workspace_bytes(m, n, k) bytes, 256-byte
- * aligned, whose first 4096 bytes are zero before the first call; with it, and with the
- * environment variable CHIMERA_GEMM_TILE=256x256x<splits> (a tuning aid), the bf16
+ * aligned, whose first 4096 bytes are zero before the first call; with it, and with a
+ * forced tile of 256x256 and splits > 1 (chimera_op_gemm_tuning), the bf16
  * kernel splits the k range over several workgroups per tile (partial sums are added in
  * a fixed order, so results stay reproducible).  Concurrent calls need separate
  * workspaces.  Without it every product runs unsplit. */
 size_t chimera_op_gemm_workspace_bytes(int m, int n, int k);
+/* Tuning aid for the bf16 matrix-core products (process-wide, affects later launches
+ * of every stage; not thread-safe against running launches).  tile_m x tile_n: 0x0 =
+ * chosen per shape (default), 128x128 or 256x256 forced; splits: 0/1 = none, 2..8 =
+ * split-K with a 256x256 forced tile and a workspace; async_mode: 0 = automatic,
+ * 1 = register-staged kernels, 2 = k-sliced 8-wavefront form for every 128x128 launch,
+ * 3 = never that form.  The initial state comes from the environment variables
+ * CHIMERA_GEMM_TILE ("256x256", "256x256x4") and CHIMERA_GEMM_ASYNC ("0", "4k", other),
+ * read once at first use.  EINVAL for any other value. */
+int chimera_op_gemm_tuning(int tile_m, int tile_n, int splits, int async_mode);
 int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind,
                     int m, int n, int k,
                     const void* d_a, int lda, int a_kc,

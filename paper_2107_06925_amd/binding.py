@@ -70,6 +70,7 @@ _SIGNATURES = {
     "chimera_model_select": (_i, [_i, _i, C.c_int64, C.c_double, C.c_double, C.c_double, _i, _i, _p, _p, _p]),
     "chimera_worker_last_enqueue_ms": (_i, [_p]),
     "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
+    "chimera_op_gemm_tuning": (_i, [_i, _i, _i, _i]),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
     "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p, _i, _p]),
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
@@ -119,7 +120,7 @@ def check(code):
 # ------------------------------------------------------------------ schedule
 def chimera_schedule(algo, D, N, rank):
     n = _sz(0)
-    cap = 2 * max(N, 1)
+    cap = 3 * max(N, 1)            # backward halving lists three ops per micro-batch
     buf = (chimera_op * cap)()
     check(lib().chimera_schedule(algo, D, N, rank, buf, cap, C.byref(n)))
     return list(buf[:n.value])

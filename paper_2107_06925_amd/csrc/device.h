@@ -101,9 +101,11 @@ __device__ __forceinline__ float gelu_grad_f(float u, int erf_form) {
 // Global -> LDS without passing through registers: lane i of the wavefront writes the 16
 // bytes it fetches from `gptr` to LDS byte address lds_base + 16 i (lds_base must be the
 // same for the whole wavefront).  Issued through inline assembly so that the wait can be
-// counted by hand (wait_vmcnt) instead of draining every outstanding load.
+// counted by hand (wait_vmcnt) instead of draining every outstanding load.  The LDS base
+// travels in M0, named as a register operand: the compiler loads M0 itself and knows that
+// the statement depends on it, so its own uses of M0 cannot collide with this one.
 __device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+    asm volatile("global_load_lds_dwordx4 %0, off" ::"v"(gptr), "{m0}"(lds_base) : "memory");
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");

@@ -689,12 +689,23 @@ struct TileChoice { int bm, bn, splits; };
 // the column sums replace bsum) instead of being added, which a single product never asks for.
 inline int epilogue_flag(const GemmArgs& g) { return g.epilogue == EPI_ACCUM_F32 ? 0 : g.gelu_erf; }
 
-TileChoice forced_tile() {
-    TileChoice c{0, 0, 0};
-    const char* e = std::getenv("CHIMERA_GEMM_TILE");   // e.g. "256x256" or "256x256x4" (x splits); tuning aid
-    if (e) std::sscanf(e, "%dx%dx%d", &c.bm, &c.bn, &c.splits);
-    return c;
+// Tuning aids, read from the environment once (first use) and changeable through
+// chimera_gemm_tuning(): a forced tile ("256x256", "128x128" or "256x256x<splits>" in
+// CHIMERA_GEMM_TILE) and the form of the LDS-DMA kernels (CHIMERA_GEMM_ASYNC: "0" = the
+// register-staged kernels, "4k" = the k-sliced 128x128 form always, "2" = never).
+enum AsyncMode { ASYNC_AUTO = 0, ASYNC_OFF = 1, ASYNC_KSLICED = 2, ASYNC_PLAIN = 3 };
+struct Tuning { TileChoice forced{0, 0, 0}; int async_mode = ASYNC_AUTO; };
+Tuning& tuning() {
+    static Tuning t = [] {
+        Tuning v;
+        if (const char* e = std::getenv("CHIMERA_GEMM_TILE")) std::sscanf(e, "%dx%dx%d", &v.forced.bm, &v.forced.bn, &v.forced.splits);
+        if (const char* e = std::getenv("CHIMERA_GEMM_ASYNC"))
+            v.async_mode = e[0] == '0' ? ASYNC_OFF : (!std::strcmp(e, "4k") ? ASYNC_KSLICED : ASYNC_PLAIN);
+        return v;
+    }();
+    return t;
 }
+TileChoice forced_tile() { return tuning().forced; }
 
 constexpr int MAX_SPLITS = 8;
 
@@ -801,8 +812,8 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     // step; then 8 wavefronts share the tile, two per 64x64 block, each taking half of every
     // k step (their partial sums meet in LDS at the end), over a 4-stage ring.  With two or
     // more workgroups per CU the 2-stage ring (64 KiB of LDS, so two workgroups fit) is faster.
-    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");                 // tuning aid: 0 = register-staged kernels
-    const bool can_async = g.k % BK == 0 && g.m >= 8 && g.n >= 8 && t.splits == 1 && !(mode && mode[0] == '0');
+    const int mode = tuning().async_mode;
+    const bool can_async = g.k % BK == 0 && g.m >= 8 && g.n >= 8 && t.splits == 1 && mode != ASYNC_OFF;
     if (can_async) {
         if (t.bm == 256 && t.bn == 256) {
             const int tm = (g.m + 255) / 256, tn = (g.n + 255) / 256;
@@ -827,7 +838,7 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
         }
         if (t.bm == 128 && t.bn == 128) {
             const long t128 = (long)((g.m + 127) / 128) * ((g.n + 127) / 128);
-            const bool ksplit = mode ? !std::strcmp(mode, "4k") : t128 < 2 * NUM_CUS;
+            const bool ksplit = mode != ASYNC_AUTO ? mode == ASYNC_KSLICED : t128 < 2 * NUM_CUS;
             if (ksplit) return launch_async<128, 128, 2, 2, 2, 3>(g, s);
             return launch_async<128, 128, 2, 2, 1, 2>(g, s);
         }
@@ -863,8 +874,8 @@ int launch_group_tiled(int count, const GemmArgs* g, float* const* bsum, int ove
     for (int i = count; i <= GROUP_MAX; ++i) grp.first[i] = tiles;
     if (tile == 256) return launch_group<256, 256, 2, 4, 1, 2>(grp, stream);
     // two workgroups per CU or the k-sliced 8-wavefront form
-    const char* mode = std::getenv("CHIMERA_GEMM_ASYNC");
-    const bool ksplit = mode ? !std::strcmp(mode, "4k") : tiles < 2 * NUM_CUS;
+    const int mode = tuning().async_mode;
+    const bool ksplit = mode != ASYNC_AUTO ? mode == ASYNC_KSLICED : tiles < 2 * NUM_CUS;
     if (ksplit) return launch_group<128, 128, 2, 2, 2, 3>(grp, stream);
     return launch_group<128, 128, 2, 2, 1, 2>(grp, stream);
 }
@@ -905,6 +916,17 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int o
     tail.c = (char*)tail.c + m0 * tail.n * sizeof(float);
     if (int rc = launch_group_tiled(count, head, bsum, overwrite, 256, s)) return rc;
     return launch_group_tiled(1, &tail, nullptr, overwrite, 128, s);   // the column sums come from the first launch
+}
+
+int gemm_mfma_set_tuning(int bm, int bn, int splits, int async_mode) {
+    if (!((bm == 0 && bn == 0) || (bm == 128 && bn == 128) || (bm == 256 && bn == 256)))
+        return fail(CHIMERA_EINVAL, "forced tile %dx%d: 0x0 (automatic), 128x128 or 256x256", bm, bn);
+    if (splits < 0 || splits > MAX_SPLITS) return fail(CHIMERA_EINVAL, "splits=%d outside [0,%d]", splits, MAX_SPLITS);
+    if (async_mode < ASYNC_AUTO || async_mode > ASYNC_PLAIN) return fail(CHIMERA_EINVAL, "async_mode=%d outside [0,3]", async_mode);
+    Tuning& t = tuning();
+    t.forced = TileChoice{bm, bn, splits};
+    t.async_mode = async_mode;
+    return CHIMERA_OK;
 }
 
 }  // namespace chimera

@@ -73,6 +73,7 @@ bool gemm_mfma_supports(const GemmArgs& g);
 // overwrite != 0: C_p and bsum_p receive the results instead of accumulating them
 bool gemm_mfma_group_supports(int count, const GemmArgs* g);
 int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream);
+int gemm_mfma_set_tuning(int bm, int bn, int splits, int async_mode);
 size_t gemm_mfma_workspace_bytes(int m, int n, int splits);
 size_t gemm_mfma_workspace_need(int m, int n, int k);   // bytes the tile heuristic wants for this shape (0 = none)
 

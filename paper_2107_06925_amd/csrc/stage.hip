@@ -829,6 +829,10 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int
 
 size_t chimera_op_gemm_workspace_bytes(int m, int n, int k) { return gemm_mfma_workspace_need(m, n, k); }
 
+int chimera_op_gemm_tuning(int tile_m, int tile_n, int splits, int async_mode) {
+    return gemm_mfma_set_tuning(tile_m, tile_n, splits, async_mode);
+}
+
 int chimera_op_gemm_group_accumulate(int count, const int* h_m, const int* h_n, int k, const void* const* h_a,
                                      const int* h_lda, const void* const* h_b, const int* h_ldb, float* const* h_c,
                                      float* const* h_bsum, int overwrite, void* hip_stream) {

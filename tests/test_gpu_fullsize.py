@@ -29,45 +29,88 @@ def _oracle_pass(cfg, params, stage_id, g, x, dy):
     return _ORACLE[key]
 
 
-def test_bert48_worker_full_size():
-    """BERT-48-like worker exactly as benchmarked: D=4, N=4, rank 0, 12 blocks per stage,
-    hidden 1024, 16 heads, seq 512, micro-batch 8, bidirectional, bf16."""
+def _worker_case(name, rank, gain, tag):
+    """One iteration of worker `rank` of the named workload through chimera_run_worker, with the stash
+    slots the schedule assigns.  Per stage one micro-batch keeps its dY - one from the middle of the
+    stage's backward order, so the overwriting first backward, accumulation after it and (for N > D)
+    a later schedule unit all lie on the checked path - and is compared with the oracle: y, dx and
+    every parameter gradient.  Micro-batches with dY = 0 must give dX = 0 exactly."""
     import torch
-    cfg = synth.CONFIGS["bert48-bf16"]
-    rank, D, N = 0, cfg.D, cfg.N
+    cfg = synth.CONFIGS[name]
+    D, N = cfg.D, cfg.N
+    ops = b.chimera_schedule(b.DIRECT, D, N, rank)
     need = b.stash_slots_needed(b.DIRECT, D, N, rank)
-    assert need == (2, 1)
-    gain = 1.0                        # the workload's own recipe, as benchmarked
+    stage_ids = (rank, D - 1 - rank)
     stages, params = [], []
-    for pipe, sid in ((0, rank), (1, D - 1 - rank)):
+    for pipe, sid in enumerate(stage_ids):
         st, p = make_stage(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, b.BF16, sid, causal=cfg.causal,
                            stash_slots=need[pipe], qk_gain=gain)
         stages.append(st), params.append(p)
-    sampled = {0: 0, 1: 3}            # pipe -> micro-batch whose dY is kept
+    pipe_of = {o.mb: o.pipe for o in ops}
+    assert sorted(pipe_of) == list(range(N))
+    sampled = {}
+    for pipe in (0, 1):
+        order = [o.mb for o in ops if o.kind == b.OP_B and o.pipe == pipe]
+        assert len(order) == N // 2
+        sampled[pipe] = order[len(order) // 2]          # neither the first nor the last backward of the stage
     xs, dys, outs = {}, {}, {}
     for g in range(N):
+        keep = sampled[pipe_of[g]] == g
         x, dy = synth.make_microbatch(cfg.tokens, cfg.hidden, g, 0, "bf16")
-        pipe = 0 if (g % D) < D // 2 else 1
-        if sampled[pipe] != g:
-            dy = np.zeros_like(dy)
-        xs[g], dys[g] = x, dy
-        outs[g] = stages[pipe].set_io(g, to_dev(x, b.BF16), to_dev(dy, b.BF16))
+        if keep:
+            xs[g], dys[g] = x, dy
+        outs[g] = stages[pipe_of[g]].set_io(g, to_dev(x, b.BF16), to_dev(dy if keep else np.zeros_like(dy), b.BF16))
     b.chimera_worker_bind(stages[0], stages[1])
     for st in stages:
         st.zero_grads()
     b.chimera_run_worker(rank, D, N)
     torch.cuda.synchronize()
+    print("%s rank %d: stash slots %s, checked micro-batches %s" % (name, rank, need, sampled), flush=True)
     for pipe, g in sampled.items():
-        y, dx, gr = _oracle_pass(cfg, params[pipe], (rank, D - 1 - rank)[pipe], g, xs[g], dys[g])
+        key = (name, stage_ids[pipe], g, gain)
+        if key not in _ORACLE:
+            print("oracle: stage %d, micro-batch %d" % (stage_ids[pipe], g), flush=True)
+            _ORACLE[key] = bo.stage_pass(xs[g], dys[g], params[pipe], cfg.microbatch, cfg.seq, cfg.heads, cfg.causal)
+        y, dx, gr = _ORACLE[key]
         ey = assert_close(to_np(outs[g][0]), y, b.BF16, "y of micro-batch %d" % g)
         ex = assert_close(to_np(outs[g][1]), dx, b.BF16, "dx of micro-batch %d" % g)
-        print("micro-batch %d: y rel err %.3e, dx rel err %.3e" % (g, ey, ex), flush=True)
         eg = compare_grads(stages[pipe].read_grads(), gr, cfg.layers, cfg.hidden, b.BF16, "stage of pipe %d" % pipe)
-        print("pipe %d: worst parameter-gradient rel err %.3e" % (pipe, eg), flush=True)
-    # micro-batches with dY = 0 give dX = 0 exactly
-    assert float(outs[1][1].float().abs().max()) == 0.0
+        print("%s %s pipe %d micro-batch %d: y %.3e, dx %.3e, worst parameter gradient %.3e" % (name, tag, pipe, g, ey, ex, eg),
+              flush=True)
+    for g in range(N):
+        if sampled[pipe_of[g]] != g:
+            assert float(outs[g][1].float().abs().max()) == 0.0, "dx of micro-batch %d (dY = 0)" % g
     for st in stages:
         st.close()
+
+
+@pytest.mark.parametrize("gained", [False, True], ids=["plain", "peaked-softmax"])
+def test_bert48_worker_full_size(gained):
+    """BERT-48-like worker exactly as benchmarked: D=4, N=4, rank 0, 12 blocks per stage, hidden 1024,
+    16 heads, seq 512, micro-batch 8, bidirectional, bf16 - once with the workload's own weights
+    (almost uniform softmax) and once with the Q, K weights scaled so that the scores are peaked."""
+    cfg = synth.CONFIGS["bert48-bf16"]
+    assert b.stash_slots_needed(b.DIRECT, cfg.D, cfg.N, 0) == (2, 1)
+    _worker_case("bert48-bf16", 0, synth.qk_gain_for(cfg.hidden) if gained else 1.0, "gained" if gained else "plain")
+
+
+# (workload, rank): rank 0 has the smallest stash (D/2+1 slots over its two stages), the middle rank
+# D/2-1 the largest (D slots, Table 2 of the paper); the middle rank runs with peaked attention scores.
+_GPT2_CASES = [("gpt2-1p3b-bf16", 0), ("gpt2-1p3b-bf16", 3), ("gpt2-1p3b-n32-bf16", 0), ("gpt2-1p3b-n32-bf16", 3),
+               ("gpt2-deep-bf16", 0), ("gpt2-deep-bf16", 15)]
+
+
+@pytest.mark.parametrize("name,rank", _GPT2_CASES, ids=["%s-rank%d" % c for c in _GPT2_CASES])
+def test_gpt2_worker_full_size(name, rank):
+    """The three GPT-2-like workloads as benchmarked: D=8 N=8 (6 blocks per stage, hidden 1600, 25
+    heads, seq 1024, micro-batch 4), D=8 N=32 (four concatenated schedule units, section 3.5 of the
+    paper, micro-batch 2) and D=32 N=32 (2 blocks per stage, hidden 2048, head dim 128, seq 2048,
+    micro-batch 1); causal, bf16; whole worker through chimera_run_worker."""
+    cfg = synth.CONFIGS[name]
+    need = b.stash_slots_needed(b.DIRECT, cfg.D, cfg.N, rank)
+    middle = rank == cfg.D // 2 - 1
+    assert sum(need) == (cfg.D if middle else cfg.D // 2 + 1)
+    _worker_case(name, rank, synth.qk_gain_for(cfg.hidden) if middle else 1.0, "peaked" if middle else "plain")
 
 
 @pytest.mark.parametrize("schedule", ["halving", "doubling"])

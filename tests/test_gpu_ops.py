@@ -108,11 +108,18 @@ def test_gemm_split_k_matches_unsplit_and_is_reproducible():
     """On request (tile override plus a workspace) the bf16 kernel splits k over several
     workgroups per tile; partial sums are added in a fixed order, so two runs agree bit
     for bit, and the result matches the oracle like the unsplit one."""
-    import os
     import torch
     m, n, k = 1024, 1024, 4096
     assert b.lib().chimera_op_gemm_workspace_bytes(m, n, k) > 0
-    os.environ["CHIMERA_GEMM_TILE"] = "256x256x4"
+    b.check(b.lib().chimera_op_gemm_tuning(256, 256, 4, 0))
+    try:
+        _split_k_body(m, n, k)
+    finally:
+        b.check(b.lib().chimera_op_gemm_tuning(0, 0, 0, 0))
+
+
+def _split_k_body(m, n, k):
+    import torch
     A, B = _rand((m, k), 1, b.BF16), _rand((k, n), 2, b.BF16)
     want = A.astype(np.float64) @ B.astype(np.float64)
     da, db = to_dev(A, b.BF16), to_dev(B, b.BF16)
@@ -130,7 +137,6 @@ def test_gemm_split_k_matches_unsplit_and_is_reproducible():
     for _ in range(2):
         b.chimera_op_gemm(at, db, dw, m, n, k, 0, 0, b.EPI_ACCUM_F32)
     assert_close(to_np(dw), 2 * want, b.BF16)
-    del os.environ["CHIMERA_GEMM_TILE"]
 
 
 GROUPS = [
