@@ -88,10 +88,10 @@ int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, 
                   float* dgamma, float* dbeta, float* scratch, int overwrite, void* stream);
 // dgamma == nullptr: the per-block partial sums stay in `scratch` ([blocks][dgamma | dbeta], the
 // size layernorm_bwd_scratch_floats gives) and layernorm_bwd_reduce finishes `count` such passes
-// of equal shape in one launch: pass y, at partial + y * part_stride, belongs to LayerNorm y & 1
+// of equal shape and element type `dtype` in one launch: pass y, at partial + y * part_stride, belongs to LayerNorm y & 1
 // of layer y >> 1, whose gradients lie at grads + layer * layer_stride + off.gamma / off.beta.
 struct LnGradOffsets { size_t gamma[2], beta[2]; };
-int layernorm_bwd_reduce(int rows, int cols, int count, const float* partial, size_t part_stride, float* grads,
+int layernorm_bwd_reduce(int dtype, int rows, int cols, int count, const float* partial, size_t part_stride, float* grads,
                          size_t layer_stride, const LnGradOffsets& off, int overwrite, void* stream);
 size_t colsum_scratch_floats(int rows, int cols);
 int colsum(int dtype, int rows, int cols, const void* x, float* out, float* scratch, void* stream);

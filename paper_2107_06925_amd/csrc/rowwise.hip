@@ -192,9 +192,13 @@ template <typename T, int V> struct RawElems {
 
 // Wide rows (more than two 16-byte chunks per lane of one wavefront): the whole workgroup
 // shares a row, so a thread keeps one chunk (MAXT of them beyond 256 chunks) instead of
-// four or eight, and the column sums of its chunks never leave its registers.  The row's
-// two sums meet in LDS, double-buffered by row parity (one barrier per row).
+// four or eight, and the column sums of its chunks never leave its registers.  A workgroup
+// takes LNW_ROWS rows and requests the operands of ALL of them before it touches any: the
+// kernel moves 16 bytes per element and does little arithmetic, so what it needs is bytes in
+// flight (about 40 KB per row here), not occupancy.  The rows' sums meet in LDS behind one
+// barrier for the whole workgroup.
 constexpr int LNW_THREADS = 256;
+constexpr int LNW_ROWS = 4;
 template <typename TX, typename TR, typename T, int MAXT>
 __global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __restrict__ dy, const TX* __restrict__ x,
                                                                   const float* __restrict__ mean,
@@ -203,10 +207,33 @@ __global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __res
                                                                   T* __restrict__ dx_lo, float* __restrict__ dx_hi,
                                                                   float* __restrict__ partial, int rows, int cols) {
     constexpr int V = Elem<T>::VEC;
-    constexpr int NW = LNW_THREADS / WAVE;
-    __shared__ float sums[2][NW][2];
+    constexpr int NW = LNW_THREADS / WAVE, R = LNW_ROWS;
+    __shared__ float sums[NW][R][2];
     const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE;
     const int nchunk = cols / V;
+    const int row0 = blockIdx.x * R;
+    const int nrow = min(R, rows - row0);                     // the same for every thread of the block
+    RawElems<T, V> r_dy[R][MAXT];
+    RawElems<TX, V> r_x[R][MAXT];
+    RawElems<TR, V> r_res[R][MAXT];
+    float mu[R], rs[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        mu[r] = 0.f; rs[r] = 0.f;
+        if (r < nrow) {
+            const size_t ro = (size_t)(row0 + r) * cols;
+            mu[r] = mean[row0 + r]; rs[r] = rstd[row0 + r];
+#pragma unroll
+            for (int t = 0; t < MAXT; ++t) {
+                const int c = tid + t * LNW_THREADS;
+                if (c < nchunk) {
+                    r_dy[r][t].load(dy + ro + c * V);
+                    r_x[r][t].load(x + ro + c * V);
+                    if (res) r_res[r][t].load(res + ro + c * V);
+                }
+            }
+        }
+    }
     float ag[MAXT][V], ab[MAXT][V], g[MAXT][V];
 #pragma unroll
     for (int t = 0; t < MAXT; ++t) {
@@ -215,79 +242,64 @@ __global__ __launch_bounds__(LNW_THREADS) void ln_bwd_wide_kernel(const T* __res
         for (int e = 0; e < V; ++e) { ag[t][e] = 0.f; ab[t][e] = 0.f; g[t][e] = 0.f; }
         if (c < nchunk) load_vec<T>(gamma + c * V, g[t]);
     }
-    const int row0 = blockIdx.x * LNB_ROWS;
-    const int nrow = min(LNB_ROWS, rows - row0);              // the same for every thread of the block
-    // The rows of a block follow each other (one barrier each), so the operands of the next
-    // row are requested, as raw 16-byte pieces, before the current row is worked on: their
-    // latency then overlaps the reductions, the barrier and the stores.
-    RawElems<T, V> n_dy[MAXT];
-    RawElems<TX, V> n_x[MAXT];
-    RawElems<TR, V> n_res[MAXT];
-    float n_mu = 0.f, n_rs = 0.f;
-    auto fetch = [&](int row) {
-        n_mu = mean[row]; n_rs = rstd[row];
+    float s1[R], s2[R];
 #pragma unroll
-        for (int t = 0; t < MAXT; ++t) {
-            const int c = tid + t * LNW_THREADS;
-            if (c < nchunk) {
-                n_dy[t].load(dy + (size_t)row * cols + c * V);
-                n_x[t].load(x + (size_t)row * cols + c * V);
-                if (res) n_res[t].load(res + (size_t)row * cols + c * V);
-            }
-        }
-    };
-    if (nrow > 0) fetch(row0);
-    for (int rr = 0; rr < nrow; ++rr) {
-        const int row = row0 + rr;
-        const float mu = n_mu, rs = n_rs;
-        RawElems<T, V> c_dy[MAXT];
-        RawElems<TX, V> c_x[MAXT];
-        RawElems<TR, V> c_res[MAXT];
+    for (int r = 0; r < R; ++r) {
+        s1[r] = 0.f; s2[r] = 0.f;
+        if (r < nrow) {
 #pragma unroll
-        for (int t = 0; t < MAXT; ++t) { c_dy[t] = n_dy[t]; c_x[t] = n_x[t]; c_res[t] = n_res[t]; }
-        if (rr + 1 < nrow) fetch(row + 1);
-        float dxh[MAXT][V], xh[MAXT][V];
-        float s1 = 0.f, s2 = 0.f;
+            for (int t = 0; t < MAXT; ++t) {
+                const int c = tid + t * LNW_THREADS;
+                if (c < nchunk) {
+                    float d[V], xv[V];
+                    r_dy[r][t].unpack(d);
+                    r_x[r][t].unpack(xv);
 #pragma unroll
-        for (int t = 0; t < MAXT; ++t) {
-            const int c = tid + t * LNW_THREADS;
-            if (c < nchunk) {
-                float d[V], xv[V];
-                c_dy[t].unpack(d);
-                c_x[t].unpack(xv);
-#pragma unroll
-                for (int e = 0; e < V; ++e) {
-                    xh[t][e] = (xv[e] - mu) * rs;
-                    dxh[t][e] = d[e] * g[t][e];
-                    s1 += dxh[t][e];
-                    s2 += dxh[t][e] * xh[t][e];
-                    ag[t][e] += d[e] * xh[t][e];
-                    ab[t][e] += d[e];
+                    for (int e = 0; e < V; ++e) {
+                        const float xh = (xv[e] - mu[r]) * rs[r];
+                        const float dxh = d[e] * g[t][e];
+                        s1[r] += dxh;
+                        s2[r] += dxh * xh;
+                        ag[t][e] += d[e] * xh;
+                        ab[t][e] += d[e];
+                    }
                 }
             }
         }
-        s1 = wave_sum(s1);
-        s2 = wave_sum(s2);
-        if (lane == 0) { sums[rr & 1][wave][0] = s1; sums[rr & 1][wave][1] = s2; }
-        __syncthreads();
+        s1[r] = wave_sum(s1[r]);
+        s2[r] = wave_sum(s2[r]);
+    }
+    if (lane == 0)
+#pragma unroll
+        for (int r = 0; r < R; ++r) { sums[wave][r][0] = s1[r]; sums[wave][r][1] = s2[r]; }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (r >= nrow) continue;
         float m1 = 0.f, m2 = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) { m1 += sums[rr & 1][w][0]; m2 += sums[rr & 1][w][1]; }
+        for (int w = 0; w < NW; ++w) { m1 += sums[w][r][0]; m2 += sums[w][r][1]; }
         m1 /= (float)cols;
         m2 /= (float)cols;
+        const size_t ro = (size_t)(row0 + r) * cols;
 #pragma unroll
         for (int t = 0; t < MAXT; ++t) {
             const int c = tid + t * LNW_THREADS;
             if (c < nchunk) {
-                float rv[V], o[V];
-                if (res) c_res[t].unpack(rv);                                            // no residual path: dx = LN'(dy)
+                float d[V], xv[V], rv[V], o[V];
+                r_dy[r][t].unpack(d);
+                r_x[r][t].unpack(xv);
+                if (res) r_res[r][t].unpack(rv);                                          // no residual path: dx = LN'(dy)
                 else
 #pragma unroll
                     for (int e = 0; e < V; ++e) rv[e] = 0.f;
 #pragma unroll
-                for (int e = 0; e < V; ++e) o[e] = rv[e] + rs * (dxh[t][e] - m1 - xh[t][e] * m2);
-                if (dx_lo) store_vec<T>(dx_lo + (size_t)row * cols + c * V, o);
-                if (dx_hi) store_elems<float, V>(dx_hi + (size_t)row * cols + c * V, o);
+                for (int e = 0; e < V; ++e) {
+                    const float xh = (xv[e] - mu[r]) * rs[r];
+                    o[e] = rv[e] + rs[r] * (d[e] * g[t][e] - m1 - xh * m2);
+                }
+                if (dx_lo) store_vec<T>(dx_lo + ro + c * V, o);
+                if (dx_hi) store_elems<float, V>(dx_hi + ro + c * V, o);
             }
         }
     }
@@ -431,13 +443,21 @@ int ln_fwd_launch(int rows, int cols, const void* x, const void* gamma, const vo
     return CHIMERA_OK;
 }
 
+// Workgroups (= partial-sum rows) of a LayerNorm backward over rows x cols elements of type T:
+// the wavefront-per-row kernel takes LNB_ROWS rows per workgroup, the wide-row kernel LNW_ROWS.
+template <typename T> int ln_bwd_blocks(int rows, int cols) {
+    const bool wide = (cols / Elem<T>::VEC + WAVE - 1) / WAVE > 2;
+    const int per = wide ? LNW_ROWS : LNB_ROWS;
+    return (rows + per - 1) / per;
+}
+
 template <typename TX, typename TR, typename T>
 int ln_bwd_launch(int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
                   const void* gamma, const void* res, void* dx_lo, float* dx_hi, float* dgamma, float* dbeta,
                   float* scratch, int overwrite, hipStream_t s) {
     constexpr int V = Elem<T>::VEC;
     const int per_lane = (cols / V + WAVE - 1) / WAVE;
-    const int nblk = (rows + LNB_ROWS - 1) / LNB_ROWS;
+    const int nblk = ln_bwd_blocks<T>(rows, cols);
     const dim3 grid(nblk), block(LN_WAVES * WAVE);
     const size_t lds = (size_t)LN_WAVES * 2 * cols * sizeof(float);
 #define LN_BWD_CASE(N)                                                                                              \
@@ -493,8 +513,10 @@ int layernorm_fwd(int dtype, int rows, int cols, const void* x, int x_f32, const
                  : ln_fwd_launch<bf16_t, bf16_t>(rows, cols, x, gamma, beta, y, mean, rstd, s);
 }
 
+// enough for either element type (a float row of `cols` has twice the chunks of a bf16 row, so
+// it may take the wide-row kernel, with fewer rows per workgroup, where the bf16 row does not)
 size_t layernorm_bwd_scratch_floats(int rows, int cols) {
-    return (size_t)((rows + LNB_ROWS - 1) / LNB_ROWS) * 2 * cols;
+    return (size_t)std::max(ln_bwd_blocks<float>(rows, cols), ln_bwd_blocks<bf16_t>(rows, cols)) * 2 * cols;
 }
 
 int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, int x_f32, const float* mean,
@@ -510,11 +532,11 @@ int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, 
 #undef LN_BWD_ARGS
 }
 
-int layernorm_bwd_reduce(int rows, int cols, int count, const float* partial, size_t part_stride, float* grads,
+int layernorm_bwd_reduce(int dtype, int rows, int cols, int count, const float* partial, size_t part_stride, float* grads,
                          size_t layer_stride, const LnGradOffsets& off, int overwrite, void* stream) {
     if (count < 1) return CHIMERA_OK;
     if (rows < 1 || cols < 1 || !partial || !grads || count > 65535) return fail(CHIMERA_EINVAL, "layernorm backward reduce: bad arguments");
-    const int nblk = (rows + LNB_ROWS - 1) / LNB_ROWS;
+    const int nblk = dtype == CHIMERA_F32 ? ln_bwd_blocks<float>(rows, cols) : ln_bwd_blocks<bf16_t>(rows, cols);
     hipLaunchKernelGGL(reduce_partials_batched_kernel, dim3((2 * cols + 31) / 32, count), dim3(256), 0, (hipStream_t)stream,
                        partial, part_stride, nblk, cols, grads, layer_stride, off, overwrite);
     CHIMERA_LAUNCH_CHECK("layernorm backward reduce (batched)");

@@ -435,7 +435,7 @@ int stage_backward(chimera_stage* st, const chimera_stage::IO& io_full, int slot
     {
         const LnGradOffsets off{{st->o_ln1_g, st->o_ln2_g}, {st->o_ln1_b, st->o_ln2_b}};
         ProfScope prof(PC_LN_BWD, 0.0, st->stream);
-        TRY(layernorm_bwd_reduce(M, H, 2 * L, lnpart, st->lnpart_floats, st->grads, st->layer_params, off, fresh, st->stream));
+        TRY(layernorm_bwd_reduce(st->dtype, M, H, 2 * L, lnpart, st->lnpart_floats, st->grads, st->layer_params, off, fresh, st->stream));
     }
     // the stash slot, the workspace and the gradient buffers are free for the next op only
     // once the side stream has drained
