@@ -393,6 +393,24 @@ int chimera_op_layernorm_bwd(int dtype, int rows, int cols, const void* d_dy,
                              const void* d_gamma, const void* d_res, void* d_dx,
                              float* d_dgamma, float* d_dbeta, float* d_scratch,
                              void* hip_stream);
+/* chimera_op_layernorm_bwd for callers that cannot allocate device memory or pass a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): same kernels and same results, but the per-block partial sums of dgamma and
+ * dbeta live in an array of the library's own, a file-scope device array of
+ * chimera_op_layernorm_bwd_noalloc_max_scratch_floats() floats (16 MiB) that every GPU the
+ * library runs on holds until the process ends.  Inputs and outputs are the caller's device
+ * buffers as above.  The call allocates nothing (no hipMalloc / hipFree, no allocating
+ * library routine); the array's device address is looked up once per device, on the first
+ * call with that device current.  ENOMEM, with nothing launched, when
+ * chimera_op_layernorm_bwd_scratch_floats(rows, cols) exceeds the array (e.g. 4096 x 2048
+ * bf16 still fits, 8192 x 2048 does not).  Every call on a GPU shares that GPU's array and its
+ * kernels overwrite the part they read, so nothing has to be cleared between calls - but
+ * calls that overlap on one GPU (different streams, or threads) race on it: serialise them. */
+size_t chimera_op_layernorm_bwd_noalloc_max_scratch_floats(void);
+int chimera_op_layernorm_bwd_noalloc(int dtype, int rows, int cols, const void* d_dy,
+                                     const void* d_x, const float* d_mean, const float* d_rstd,
+                                     const void* d_gamma, const void* d_res, void* d_dx,
+                                     float* d_dgamma, float* d_dbeta, void* hip_stream);
 /* out[cols] (float) += sum over rows of x[rows, cols]. */
 size_t chimera_op_colsum_scratch_floats(int rows, int cols);
 int chimera_op_colsum(int dtype, int rows, int cols, const void* d_x, float* d_out,

@@ -76,6 +76,8 @@ _SIGNATURES = {
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
     "chimera_op_layernorm_bwd_scratch_floats": (_sz, [_i, _i]),
     "chimera_op_layernorm_bwd": (_i, [_i, _i, _i] + [_p] * 11),
+    "chimera_op_layernorm_bwd_noalloc_max_scratch_floats": (_sz, []),
+    "chimera_op_layernorm_bwd_noalloc": (_i, [_i, _i, _i] + [_p] * 10),
     "chimera_op_colsum_scratch_floats": (_sz, [_i, _i]),
     "chimera_op_colsum": (_i, [_i, _i, _i, _p, _p, _p, _p]),
     "chimera_op_attention_fwd": (_i, [_i] * 7 + [_p, _p, _p, _p]),
@@ -427,6 +429,12 @@ def chimera_op_layernorm_bwd(dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta):
     scratch = torch.empty(lib().chimera_op_layernorm_bwd_scratch_floats(rows, cols), dtype=torch.float32, device=x.device)
     check(lib().chimera_op_layernorm_bwd(_dt(x), rows, cols, _ptr(dy), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma),
                                          _ptr(res), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), _stream(x)))
+
+
+def chimera_op_layernorm_bwd_noalloc(dy, x, mean, rstd, gamma, res, dx, dgamma, dbeta):
+    rows, cols = x.shape
+    check(lib().chimera_op_layernorm_bwd_noalloc(_dt(x), rows, cols, _ptr(dy), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma),
+                                                 _ptr(res), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _stream(x)))
 
 
 def chimera_op_colsum(x, out):

@@ -86,6 +86,11 @@ size_t layernorm_bwd_scratch_floats(int rows, int cols);
 int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, int x_f32, const float* mean,
                   const float* rstd, const void* gamma, const void* res, int res_f32, void* dx_lo, float* dx_hi,
                   float* dgamma, float* dbeta, float* scratch, int overwrite, void* stream);
+// The same with the partial sums in the library's static device array (no workspace argument, no allocation);
+// ENOMEM when layernorm_bwd_scratch_floats(rows, cols) exceeds layernorm_bwd_static_scratch_floats().
+size_t layernorm_bwd_static_scratch_floats();
+int layernorm_bwd_noalloc(int dtype, int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
+                          const void* gamma, const void* res, void* dx, float* dgamma, float* dbeta, void* stream);
 // dgamma == nullptr: the per-block partial sums stay in `scratch` ([blocks][dgamma | dbeta], the
 // size layernorm_bwd_scratch_floats gives) and layernorm_bwd_reduce finishes `count` such passes
 // of equal shape and element type `dtype` in one launch: pass y, at partial + y * part_stride, belongs to LayerNorm y & 1

@@ -6,6 +6,15 @@
 // not depend on scheduling.
 #include "device.h"
 
+#include <mutex>
+
+// Scratch of chimera_op_layernorm_bwd_noalloc: the per-block partial sums of dgamma and
+// dbeta, held by every GPU the library runs on until the process ends.  Host code never
+// uses this name as an address; it asks the runtime for the array's device address once
+// per device (static_scratch below).
+constexpr size_t LN_STATIC_SCRATCH_FLOATS = (size_t)4 << 20;        // 16 MiB
+static __device__ __align__(256) float scratch[LN_STATIC_SCRATCH_FLOATS];
+
 namespace chimera {
 
 namespace {
@@ -530,6 +539,41 @@ int layernorm_bwd(int dtype, int rows, int cols, const void* dy, const void* x, 
     if (x_f32) return res_f32 ? ln_bwd_launch<float, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<float, bf16_t, bf16_t>(LN_BWD_ARGS);
     return res_f32 ? ln_bwd_launch<bf16_t, float, bf16_t>(LN_BWD_ARGS) : ln_bwd_launch<bf16_t, bf16_t, bf16_t>(LN_BWD_ARGS);
 #undef LN_BWD_ARGS
+}
+
+// Device address of the static scratch array on the current device, looked up once per
+// device (each GPU holds its own copy at its own address).
+int static_scratch(float** out) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static float* ptr[MAX_DEVICES] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(CHIMERA_EDEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(CHIMERA_EDEVICE, "device index %d outside [0,%d)", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        float* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(CHIMERA_EDEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return CHIMERA_OK;
+}
+
+size_t layernorm_bwd_static_scratch_floats() { return LN_STATIC_SCRATCH_FLOATS; }
+
+int layernorm_bwd_noalloc(int dtype, int rows, int cols, const void* dy, const void* x, const float* mean, const float* rstd,
+                          const void* gamma, const void* res, void* dx, float* dgamma, float* dbeta, void* stream) {
+    if (int rc = check_rowwise(dtype, rows, cols)) return rc;
+    const size_t need = layernorm_bwd_scratch_floats(rows, cols);
+    if (need > LN_STATIC_SCRATCH_FLOATS)
+        return fail(CHIMERA_ENOMEM, "layernorm backward of %d x %d needs %zu scratch floats, the static scratch holds %zu",
+                    rows, cols, need, (size_t)LN_STATIC_SCRATCH_FLOATS);
+    float* sc = nullptr;
+    if (int rc = static_scratch(&sc)) return rc;
+    return layernorm_bwd(dtype, rows, cols, dy, x, 0, mean, rstd, gamma, res, 0, dx, nullptr, dgamma, dbeta, sc, 0, stream);
 }
 
 int layernorm_bwd_reduce(int dtype, int rows, int cols, int count, const float* partial, size_t part_stride, float* grads,

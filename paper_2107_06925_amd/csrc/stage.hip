@@ -868,6 +868,16 @@ int chimera_op_layernorm_bwd(int dtype, int rows, int cols, const void* d_dy, co
                          0, hip_stream);
 }
 
+size_t chimera_op_layernorm_bwd_noalloc_max_scratch_floats(void) { return layernorm_bwd_static_scratch_floats(); }
+
+int chimera_op_layernorm_bwd_noalloc(int dtype, int rows, int cols, const void* d_dy, const void* d_x, const float* d_mean,
+                                     const float* d_rstd, const void* d_gamma, const void* d_res, void* d_dx,
+                                     float* d_dgamma, float* d_dbeta, void* hip_stream) {
+    if (!d_dy || !d_x || !d_mean || !d_rstd || !d_gamma || !d_res || !d_dx || !d_dgamma || !d_dbeta)
+        return fail(CHIMERA_EINVAL, "NULL operand");
+    return layernorm_bwd_noalloc(dtype, rows, cols, d_dy, d_x, d_mean, d_rstd, d_gamma, d_res, d_dx, d_dgamma, d_dbeta, hip_stream);
+}
+
 size_t chimera_op_colsum_scratch_floats(int rows, int cols) { return colsum_scratch_floats(rows, cols); }
 
 int chimera_op_colsum(int dtype, int rows, int cols, const void* d_x, float* d_out, float* d_scratch, void* hip_stream) {
