@@ -20,47 +20,44 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix throughput
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the grouped weight-gradient kernel, from two rocprofv3 --pmc runs of
-# this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the kernel's
-# launches), each scaled by what the same counter reads for a streaming kernel of known size
-# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00): (114950.1 * 2.00 + 49215.9) KiB.
+PROFILES = os.path.join(ROOT, "profiles")
 
 
-def _group_kernel_params(hidden):
-    """Template arguments of the grouped weight-gradient kernel the library picks for a block of this width
-    (its rule: 256x256 tiles once the four products have 160 of them, else 128x128; the 128x128 form is
-    k-sliced over 8 wavefronts below 512 tiles)."""
-    t = lambda n, tile: -(-n // tile)
-    shapes = [(hidden, 3 * hidden), (hidden, hidden), (hidden, 4 * hidden), (4 * hidden, hidden)]
-    if sum(t(m, 256) * t(n, 256) for m, n in shapes) >= 160:
-        return "256,256,2,4,1,2"
-    return "128,128,2,2,2,3" if sum(t(m, 128) * t(n, 128) for m, n in shapes) < 512 else "128,128,2,2,1,2"
+def _roofline_traffic(workload):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary of this
+    workload (profiles/bench_<workload>_hbm_traffic.txt, line `roofline_traffic_bytes_per_launch = N`);
+    None when no summary exists for it."""
+    path = os.path.join(PROFILES, "bench_%s_hbm_traffic.txt" % workload.replace("-bf16", "").replace("-", "_"))
+    try:
+        with open(path) as f:
+            for line in f:
+                if "roofline_traffic_bytes_per_launch" in line and "=" in line:
+                    return int(float(line.split("=")[1].split()[0]))
+    except OSError:
+        pass
+    return None
 
 
-WGRAD_TRAFFIC_BYTES = {"bert48-bf16": int((114950.1 * 2.00 + 49215.9) * 1024)}
-
-
-def _cpu_baseline(cfg, blocks=6):
-    """The oracle as it stands, timed on the host cores: one micro-batch forward +
-    backward through `blocks` of the stage's Transformer blocks at full shape."""
-    import numpy as np
+def _cpu_baseline(cfg):
+    """The oracle as it stands, timed on the host cores: one micro-batch forward + backward through a whole
+    stage (all of its Transformer blocks) at full shape.  An iteration is N such stage passes, so
+    sequences/s = N*B / (N * t_pass) = B / t_pass."""
     from threadpoolctl import threadpool_info
     from oracle import block_oracle as bo
     from paper_2107_06925_amd import synth
-    params = synth.make_stage_params(cfg.hidden, blocks, 0, seed=0, dtype=cfg.dtype)
+    params = synth.make_stage_params(cfg.hidden, cfg.layers, 0, seed=0, dtype=cfg.dtype)
     x, dy = synth.make_microbatch(cfg.tokens, cfg.hidden, 0, seed=0, dtype=cfg.dtype)
     t0 = time.perf_counter()
     bo.stage_pass(x, dy, params, cfg.microbatch, cfg.seq, cfg.heads, cfg.causal)
     dt = time.perf_counter() - t0
-    stage_pass_s = dt * cfg.layers / blocks            # a full stage has cfg.layers blocks
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {
-        "value": cfg.microbatch / stage_pass_s,         # = N*B / (N stage passes)
+        "value": cfg.microbatch / dt,
         "unit": "sequences/s",
         "cores": int(threads),
         "kind": "oracle",
-        "sample": "1 micro-batch (%d sequences) forward+backward through %d of the stage's %d blocks at full shape, "
-                  "fp64 numpy, %.1f s; scaled to the whole stage" % (cfg.microbatch, blocks, cfg.layers, dt),
+        "sample": "1 of the iteration's %d micro-batches (%d sequences) forward+backward through one whole stage "
+                  "(%d blocks) at full shape, fp64 numpy, %.1f s" % (cfg.N, cfg.microbatch, cfg.layers, dt),
     }
 
 
@@ -110,7 +107,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="bert48-bf16")
+    ap.add_argument("--config", default="gpt2-1p3b-n32-bf16", help="workload (default: the largest single-GPU one, 76 TFLOP per iteration)")
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
@@ -214,18 +211,19 @@ def main():
         wg = prof["gemm_wgrad"]
         achieved = wg["work"] / (wg["ms"] * 1e-3) / 1e12 if wg["ms"] else 0.0
         out["roofline"] = {
-            "kernel": ("gemm_bf16_async_group_kernel<%s,0,0> (the four weight gradients of a block, "
-                       "dW += X^T dY in fp32, and their bias gradients, one launch per block and micro-batch)"
-                       % _group_kernel_params(cfg.hidden)
+            "kernel": ("%s (the four weight gradients of a block, dW += X^T dY in fp32, and their bias gradients, per block "
+                       "and micro-batch; the figures are those of the first instantiation named)"
+                       % b.lib().chimera_op_gemm_group_last_kernel().decode()
                        if dtype == b.BF16 else "gemm_ref_kernel (weight-gradient GEMMs)"),
             "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-            "traffic": WGRAD_TRAFFIC_BYTES.get(cfg.name) if not args.no_overlap else None,
+            "traffic": _roofline_traffic(cfg.name) if (not args.no_overlap and algo == b.DIRECT and f == 1 and rank == 0) else None,
             "launches_per_step": wg["launches"], "avg_launch_us": wg["ms"] * 1e3 / max(wg["launches"], 1),
             "flop_per_launch": wg["work"] / max(wg["launches"], 1),
         }
-        gemm_ms = sum(prof[k]["ms"] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
-        gemm_flop = sum(prof[k]["work"] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"))
+        gemm_classes = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "gemm_wgrad_tail")
+        gemm_ms = sum(prof[k]["ms"] for k in gemm_classes)
+        gemm_flop = sum(prof[k]["work"] for k in gemm_classes)
         all_tf = gemm_flop / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0
         out["all_stage_gemms"] = {"TFLOP/s": all_tf, "frac_mfma_peak": all_tf / MFMA_BF16_PEAK_TFLOPS,
                                   "flop_per_step": gemm_flop, "ms": gemm_ms}

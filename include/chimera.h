@@ -319,9 +319,11 @@ int chimera_worker_last_enqueue_ms(double* h_ms);
  * event pair brackets every launch (this slows the replay a little, so keep it
  * off when timing whole iterations).  Classes: 0 GEMM forward, 1 GEMM dgrad,
  * 2 GEMM wgrad, 3 attention forward, 4 attention backward, 5 LayerNorm forward,
- * 6 LayerNorm backward, 7 column sums.  chimera_profile_read must be called
+ * 6 LayerNorm backward, 7 column sums, 8 the second launch of a block's weight
+ * gradients (row bands that leave the 256x256 launch for smaller tiles; class 2 is
+ * then the first launch alone).  chimera_profile_read must be called
  * with the stream idle; it returns the summed milliseconds, the number of
- * launches and the summed algorithmic work (flop for classes 0-4, bytes for
+ * launches and the summed algorithmic work (flop for classes 0-4 and 8, bytes for
  * 5-7) since the last chimera_profile_reset. */
 int chimera_profile_enable(int on);
 int chimera_profile_reset(void);
@@ -356,6 +358,12 @@ size_t chimera_op_gemm_workspace_bytes(int m, int n, int k);
  * CHIMERA_GEMM_TILE ("256x256", "256x256x4") and CHIMERA_GEMM_ASYNC ("0", "4k", other),
  * read once at first use.  EINVAL for any other value. */
 int chimera_op_gemm_tuning(int tile_m, int tile_n, int splits, int async_mode);
+/* For reports: the kernel instantiation(s) the calling thread's last grouped launch
+ * (chimera_op_gemm_group_accumulate, or a block's weight gradients inside chimera_bwd) went
+ * to, e.g. "gemm_bf16_async_group_kernel<256,256,2,4,1,2,false,false>"; two names joined by
+ * " + " when the last row bands went out as a second launch.  Thread-local static storage,
+ * never freed by the caller; "" before the first such launch. */
+const char* chimera_op_gemm_group_last_kernel(void);
 int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind,
                     int m, int n, int k,
                     const void* d_a, int lda, int a_kc,

@@ -71,6 +71,7 @@ _SIGNATURES = {
     "chimera_worker_last_enqueue_ms": (_i, [_p]),
     "chimera_op_gemm_workspace_bytes": (_sz, [_i, _i, _i]),
     "chimera_op_gemm_tuning": (_i, [_i, _i, _i, _i]),
+    "chimera_op_gemm_group_last_kernel": (C.c_char_p, []),
     "chimera_op_gemm": (_i, [_i] * 7 + [_p, _i, _i, _p, _i, _i, _p, _p, _p, _p, _p, _sz, _p]),
     "chimera_op_gemm_group_accumulate": (_i, [_i, _p, _p, _i, _p, _p, _p, _p, _p, _p, _i, _p]),
     "chimera_op_layernorm_fwd": (_i, [_i, _i, _i, _p, _p, _p, _p, _p, _p, _p]),
@@ -326,7 +327,7 @@ def chimera_worker_last_enqueue_ms():
     return v.value
 
 
-PROFILE_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum")
+PROFILE_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "gemm_wgrad_tail")
 
 
 def chimera_profile_enable(on):

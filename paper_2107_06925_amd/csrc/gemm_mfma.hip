@@ -35,8 +35,10 @@
 // that the tiles in flight on one XCD share operand panels in its L2.
 #include "device.h"
 
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 namespace chimera {
 
@@ -147,6 +149,34 @@ __device__ __forceinline__ void load8(const float* p, float* o) { load_vec<float
 __device__ __forceinline__ void store8(bf16_t* p, const float* v) { store_vec<bf16_t>(p, v); }
 __device__ __forceinline__ void store8(float* p, const float* v) { store_vec<float>(p, v); store_vec<float>(p + 4, v + 4); }
 
+// 8 consecutive elements as they come from memory (one or two 16-byte pieces), widened later:
+// what the epilogue requests ahead of time.
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    uint4 q;
+    __device__ __forceinline__ void load(const bf16_t* p) { q = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void unpack(float* o) const {
+        const unsigned w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { o[2 * i] = __uint_as_float(w[i] << 16); o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+    }
+};
+template <> struct Raw8<float> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const float* p) {
+        lo = *reinterpret_cast<const float4*>(p); hi = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ void unpack(float* o) const {
+        o[0] = lo.x; o[1] = lo.y; o[2] = lo.z; o[3] = lo.w; o[4] = hi.x; o[5] = hi.y; o[6] = hi.z; o[7] = hi.w;
+    }
+};
+
+// The operand an epilogue reads from memory besides the bias: the residual, the GeLU input, or
+// the old value of a float accumulator.  Each band of 32 rows needs 32 / RPP pieces per lane, and
+// a piece that is only requested when its turn comes costs a full memory round trip per pass
+// (16 in a row for a 128-row wavefront tile: as long as a short k loop).  So the pieces of the
+// next DEPTH bands are requested before the current band is worked on: all bands when the
+// elements have 2 bytes, two bands when they are floats (registers).
 template <int EPI, bool RF32, bool CF32, int TM, int TN>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* slab, int row_base, int col_base, int m,
                                          int n, const bf16_t* __restrict__ bias, const bf16_t* __restrict__ R,
@@ -154,19 +184,45 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
     constexpr int WN = EpiSlab<TN>::WN, STRIDE = EpiSlab<TN>::STRIDE;
     constexpr int CPR = WN / 8;                // 8-column pieces per row
     constexpr int RPP = 64 / CPR;              // rows covered by the 64 lanes at once
+    constexpr int NP = 32 / RPP;               // passes per band of 32 rows
+    constexpr bool READS_F32 = EPI == EPI_ACCUM_F32 || (EPI == EPI_BIAS_RESIDUAL && RF32);
+    constexpr bool READS = EPI == EPI_BIAS_RESIDUAL || EPI == EPI_DGELU || EPI == EPI_ACCUM_F32;
+    using RT = std::conditional_t<READS_F32, float, bf16_t>;
+    constexpr int DEPTH = !READS ? 1 : (READS_F32 ? (TM < 2 ? TM : 2) : TM);
     bf16_t* C = (bf16_t*)c;
     float* Cf = (float*)c;
-    const float* Rf = reinterpret_cast<const float*>(R);
     const int l32 = lane & 31, lhi = lane >> 5;
     const int pr = lane / CPR, pc = (lane % CPR) * 8;
     const int gcol = col_base + pc;
+    const bool reads = READS && !(EPI == EPI_ACCUM_F32 && epi_flag);      // an overwriting accumulate reads nothing
+    const RT* Rsrc = EPI == EPI_ACCUM_F32 ? reinterpret_cast<const RT*>(c) : reinterpret_cast<const RT*>(R);
+    // pieces outside the matrix are requested from its last row / last piece (never used)
+    const int lcol = min(gcol, n - 8);
+    Raw8<RT> ahead[DEPTH][NP];
+    auto request = [&](int a, auto slot_c) {
+        constexpr int SLOT = decltype(slot_c)::value;
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            const int grow = min(row_base + a * 32 + j * RPP + pr, m - 1);
+            ahead[SLOT][j].load(Rsrc + (size_t)grow * n + lcol);
+        }
+    };
     float bv[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) bv[e] = 0.f;
     if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RESIDUAL)
         if (gcol < n) load8(bias + gcol, bv);
-#pragma unroll
-    for (int a = 0; a < TM; ++a) {
+    if constexpr (READS)
+        if (reads) {
+            request(0, std::integral_constant<int, 0>{});
+            if constexpr (DEPTH > 1 && TM > 1) request(1, std::integral_constant<int, 1 % DEPTH>{});
+            if constexpr (DEPTH > 2 && TM > 2) request(2, std::integral_constant<int, 2 % DEPTH>{});
+            if constexpr (DEPTH > 3 && TM > 3) request(3, std::integral_constant<int, 3 % DEPTH>{});
+        }
+    static_assert(TM <= 4, "at most four bands per wavefront");
+    auto band = [&](auto a_c) {
+        constexpr int a = decltype(a_c)::value;
+        constexpr int SLOT = a % DEPTH;
 #pragma unroll
         for (int b = 0; b < TN; ++b)
 #pragma unroll
@@ -174,12 +230,19 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
         __builtin_amdgcn_s_waitcnt(0xc07f);                   // lgkmcnt(0): the slab is written (wavefront-private)
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int j = 0; j < 32 / RPP; ++j) {
+        for (int j = 0; j < NP; ++j) {
             const int lr = j * RPP + pr;
             const int grow = row_base + a * 32 + lr;
             float v[8];
             load_vec<float>(slab + lr * STRIDE + pc, v);
             load_vec<float>(slab + lr * STRIDE + pc + 4, v + 4);
+            float rv[8];
+            if constexpr (READS) {
+                if (reads) ahead[SLOT][j].unpack(rv);
+                else
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) rv[e] = 0.f;
+            }
             if (grow >= m || gcol >= n) continue;
             const size_t idx = (size_t)grow * n + gcol;
             if constexpr (EPI == EPI_NONE) {
@@ -202,34 +265,32 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[TM][TN], float* sla
                 store8(C + idx, v);
                 store8(C2 + idx, g);
             } else if constexpr (EPI == EPI_BIAS_RESIDUAL) {
-                float rv[8];
-                if constexpr (RF32) load8(Rf + idx, rv); else load8(R + idx, rv);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] += bv[e] + rv[e];
                 if constexpr (CF32) store8(Cf + idx, v); else store8(C + idx, v);
             } else if constexpr (EPI == EPI_DGELU) {
-                float u[8];
-                load8(R + idx, u);
                 if (epi_flag) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], 1);
+                    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(rv[e], 1);
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e], 0);
+                    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(rv[e], 0);
                 }
                 store8(C + idx, v);
             } else {
-                if (!epi_flag) {               // accumulate; with the flag set the result replaces C
-                    float old[8];
-                    load8(Cf + idx, old);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] += old[e];
-                }
+                for (int e = 0; e < 8; ++e) v[e] += rv[e];    // rv = 0 when the result replaces C
                 store8(Cf + idx, v);
             }
         }
         __builtin_amdgcn_wave_barrier();                      // all lanes have read the slab before it is rewritten
-    }
+        if constexpr (READS && a + DEPTH < TM)
+            if (reads) request(a + DEPTH, std::integral_constant<int, SLOT>{});
+    };
+    band(std::integral_constant<int, 0>{});
+    if constexpr (TM > 1) band(std::integral_constant<int, 1>{});
+    if constexpr (TM > 2) band(std::integral_constant<int, 2>{});
+    if constexpr (TM > 3) band(std::integral_constant<int, 3>{});
 }
 
 template <int BM, int BN, int WGM, int WGN, int PF, bool A_KC, bool B_KC>
@@ -406,7 +467,7 @@ template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_K
 __device__ __forceinline__ void gemm_async_tile(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int epi_flag, int res_types, int tiles_m, int tiles_n, int block_id,
+    int ldb, int epi, int epi_flag, int res_types, int tiles_m, int tiles_n, int group_m, int block_id,
     float* __restrict__ bsum = nullptr, bool xcd_remap = true) {
     constexpr int NT = WGM * WGN * WGK * 64;
     constexpr int KSUB = BK / 16 / WGK;                                   // 16-wide k slices per wavefront and step
@@ -421,9 +482,9 @@ __device__ __forceinline__ void gemm_async_tile(
     // `block_id` as the hardware deals it (round-robin over the XCDs) or already renumbered
     const int xcd = block_id & 7, local = block_id >> 3;
     const int pid = xcd_remap ? xcd * (nblk >> 3) + min(xcd, nblk & 7) + local : block_id;
-    const int width = GROUP_M * tiles_n;
-    const int first_m = (pid / width) * GROUP_M;
-    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int width = group_m * tiles_n;
+    const int first_m = (pid / width) * group_m;
+    const int gsz = min(tiles_m - first_m, group_m);
     const int tile_m = first_m + (pid % width) % gsz;
     const int tile_n = (pid % width) / gsz;
     const int i0 = tile_m * BM, j0 = tile_n * BN;
@@ -625,9 +686,9 @@ template <int BM, int BN, int WGM, int WGN, int WGK, int NS, bool A_KC, bool B_K
 __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ R, void* __restrict__ C, bf16_t* __restrict__ C2, int m, int n, int k, int lda,
-    int ldb, int epi, int epi_flag, int res_types, int tiles_m, int tiles_n) {
+    int ldb, int epi, int epi_flag, int res_types, int tiles_m, int tiles_n, int group_m) {
     gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, -1>(A, B, bias, R, C, C2, m, n, k, lda, ldb, epi, epi_flag,
-                                                                res_types, tiles_m, tiles_n, (int)blockIdx.x);
+                                                                res_types, tiles_m, tiles_n, group_m, (int)blockIdx.x);
 }
 
 // Several products C_p (float) += A_p B_p of one launch: same contraction length and operand
@@ -641,6 +702,7 @@ struct GemmGroup {
     float* c[GROUP_MAX];
     float* bsum[GROUP_MAX];      // optional: bsum[j] += sum_k B(k, j)
     int m[GROUP_MAX], n[GROUP_MAX], lda[GROUP_MAX], ldb[GROUP_MAX], tiles_m[GROUP_MAX], tiles_n[GROUP_MAX];
+    int group_m[GROUP_MAX];      // tile rows per raster group of each product
     int first[GROUP_MAX + 1];
     int count, k;
     int overwrite;               // results replace C and bsum instead of being added
@@ -659,7 +721,8 @@ __global__ __launch_bounds__(WGM* WGN * WGK * 64) void gemm_bf16_async_group_ker
         if (i < grp.count && gid >= grp.first[i]) p = i;
     gemm_async_tile<BM, BN, WGM, WGN, WGK, NS, A_KC, B_KC, EPI_ACCUM_F32>(
         grp.a[p], grp.b[p], nullptr, nullptr, grp.c[p], nullptr, grp.m[p], grp.n[p], grp.k, grp.lda[p], grp.ldb[p],
-        EPI_ACCUM_F32, grp.overwrite, 0, grp.tiles_m[p], grp.tiles_n[p], gid - grp.first[p], grp.bsum[p], false);
+        EPI_ACCUM_F32, grp.overwrite, 0, grp.tiles_m[p], grp.tiles_n[p], grp.group_m[p], gid - grp.first[p], grp.bsum[p],
+        false);
 }
 
 // A launch of 256x256 tiles runs in rounds of NUM_CUS tiles, and a last round with few tiles
@@ -680,6 +743,28 @@ int bands_to_peel(long other, int tm, int tn, int n) {
         if (est < best) { best = est; best_b = b; }
     }
     return best_b;
+}
+
+// Tile rows per raster group.  A launch's tiles are dealt to the 8 XCDs in contiguous ranges of
+// `per_xcd` tiles, walked column by column inside groups of g tile rows, so an XCD works on
+// about g rows x per_xcd / g columns of tiles and its L2 has to fetch g row panels of A and
+// per_xcd / g column panels of B - everything an L2 misses arrives at HBM speed (about 7 TB/s
+// for the whole chip, a quarter of what the L2s deliver), whether or not it is in the memory-
+// side cache.  Returns the g that minimises the bytes fetched (tile heights bm, widths bn),
+// counting the ragged last group at its share of the rows.
+int raster_group(int tiles_m, int tiles_n, int per_xcd, int bm, int bn) {
+    int best_g = 1;
+    double best = 1e300;
+    for (int g = 1; g <= std::min(tiles_m, 16); ++g) {
+        double cost = 0;
+        for (int r0 = 0; r0 < tiles_m; r0 += g) {
+            const int rows = std::min(g, tiles_m - r0);
+            const int cols = std::min(tiles_n, (per_xcd + rows - 1) / rows);
+            cost += ((double)rows * bm + (double)cols * bn) * rows;       // weighted by the group's share of the tiles
+        }
+        if (cost < best * 0.999) { best = cost; best_g = g; }
+    }
+    return best_g;
 }
 
 struct TileChoice { int bm, bn, splits; };
@@ -726,7 +811,8 @@ TileChoice choose_tile(const GemmArgs& g) {
         if (f.splits > 1 && (!g.ws || g.ws_bytes < gemm_mfma_workspace_bytes(g.m, g.n, f.splits))) f.splits = 1;
         return f;
     }
-    if (t256 >= 160) return {256, 256, 1};
+    // (measured at 2048 x 4800 x 1600: 152 tiles of 256x256 on 256 CUs take 42 us, 608 of 128x128 48 us)
+    if (t256 >= 144) return {256, 256, 1};
     return {128, 128, 1};
 }
 
@@ -753,11 +839,12 @@ template <int BM, int BN, int WGM, int WGN, int WGK, int NS>
 int launch_async(const GemmArgs& g, hipStream_t s) {
     const int tm = (g.m + BM - 1) / BM, tn = (g.n + BN - 1) / BN;
     const dim3 grid(tm * tn), block(WGM * WGN * WGK * 64);
+    const int gm = raster_group(tm, tn, (tm * tn + 7) / 8, BM, BN);
 #define CHIMERA_GEMM_LAUNCH(AKC, BKC)                                                                                \
     hipLaunchKernelGGL((gemm_bf16_async_kernel<BM, BN, WGM, WGN, WGK, NS, AKC, BKC>), grid, block, 0, s,                   \
                        (const bf16_t*)g.a, (const bf16_t*)g.b, (const bf16_t*)g.bias, (const bf16_t*)g.r, g.c,        \
                        (bf16_t*)g.c2, g.m, g.n, g.k, g.lda, g.ldb, g.epilogue, epilogue_flag(g),                            \
-                       (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn)
+                       (g.r_f32 ? 1 : 0) | (g.c_f32 ? 2 : 0), tm, tn, gm)
     if (g.a_kc && !g.b_kc) CHIMERA_GEMM_LAUNCH(true, false);
     else if (g.a_kc && g.b_kc) CHIMERA_GEMM_LAUNCH(true, true);
     else CHIMERA_GEMM_LAUNCH(false, false);
@@ -766,8 +853,19 @@ int launch_async(const GemmArgs& g, hipStream_t s) {
     return CHIMERA_OK;
 }
 
+// Name of the kernel instantiation(s) the last grouped launch on this thread went to (for reports).
+thread_local char g_last_group_kernel[192] = "";
+void note_group_kernel(bool first, const char* name) {
+    char* dst = g_last_group_kernel;
+    const size_t used = first ? 0 : std::strlen(dst);
+    std::snprintf(dst + used, sizeof g_last_group_kernel - used, "%s%s", used ? " + " : "", name);
+}
+
 template <int BM, int BN, int WGM, int WGN, int WGK, int NS>
-int launch_group(const GemmGroup& grp, hipStream_t s) {
+int launch_group(const GemmGroup& grp, hipStream_t s, bool first = true) {
+    char name[96];
+    std::snprintf(name, sizeof name, "gemm_bf16_async_group_kernel<%d,%d,%d,%d,%d,%d,false,false>", BM, BN, WGM, WGN, WGK, NS);
+    note_group_kernel(first, name);
     const dim3 grid(grp.first[grp.count]), block(WGM * WGN * WGK * 64);
     hipLaunchKernelGGL((gemm_bf16_async_group_kernel<BM, BN, WGM, WGN, WGK, NS, false, false>), grid, block, 0, s, grp);
     CHIMERA_LAUNCH_CHECK("bf16 gemm group");
@@ -859,7 +957,8 @@ bool gemm_mfma_group_supports(int count, const GemmArgs* g) {
 }
 
 namespace {
-int launch_group_tiled(int count, const GemmArgs* g, float* const* bsum, int overwrite, int tile, hipStream_t stream) {
+int launch_group_tiled(int count, const GemmArgs* g, float* const* bsum, int overwrite, int tile, hipStream_t stream,
+                       bool first = true) {
     GemmGroup grp{};
     grp.count = count; grp.k = g[0].k; grp.overwrite = overwrite ? 1 : 0;
     int tiles = 0;
@@ -871,20 +970,27 @@ int launch_group_tiled(int count, const GemmArgs* g, float* const* bsum, int ove
         grp.first[i] = tiles;
         tiles += grp.tiles_m[i] * grp.tiles_n[i];
     }
+    for (int i = 0; i < count; ++i) grp.group_m[i] = raster_group(grp.tiles_m[i], grp.tiles_n[i], (tiles + 7) / 8, tile, tile);
     for (int i = count; i <= GROUP_MAX; ++i) grp.first[i] = tiles;
-    if (tile == 256) return launch_group<256, 256, 2, 4, 1, 2>(grp, stream);
+    if (tile == 256) return launch_group<256, 256, 2, 4, 1, 2>(grp, stream, first);
     // two workgroups per CU or the k-sliced 8-wavefront form
     const int mode = tuning().async_mode;
     const bool ksplit = mode != ASYNC_AUTO ? mode == ASYNC_KSLICED : tiles < 2 * NUM_CUS;
-    if (ksplit) return launch_group<128, 128, 2, 2, 2, 3>(grp, stream);
-    return launch_group<128, 128, 2, 2, 1, 2>(grp, stream);
+    if (ksplit) return launch_group<128, 128, 2, 2, 2, 3>(grp, stream, first);
+    return launch_group<128, 128, 2, 2, 1, 2>(grp, stream, first);
 }
 }  // namespace
 
-int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream) {
+// Decides how a group goes out: tile size, and whether the last row bands of one product leave
+// as a second launch with 128x128 tiles (a nearly empty last round of 256x256 tiles).
+int gemm_mfma_group_plan(int count, const GemmArgs* g, GemmGroupPlan* plan) {
+    if (!plan) return fail(CHIMERA_EINVAL, "plan is NULL");
     if (!gemm_mfma_group_supports(count, g))
         return fail(CHIMERA_EINVAL, "bf16 gemm group: 1..%d float-accumulating products with index-contiguous operands, "
                     "one contraction length (a multiple of %d)", GROUP_MAX, BK);
+    static_assert(GROUP_MAX == sizeof(plan->head) / sizeof(plan->head[0]), "plan size");
+    plan->count = count; plan->has_tail = 0; plan->tail_of = -1;
+    for (int i = 0; i < count; ++i) plan->head[i] = g[i];
     // tile choice as for single products: 256x256 once such tiles occupy most of the chip, else
     // 128x128.  (192 tiles of 256x256 on 256 CUs beat 768 tiles of 128x128: they pull half the
     // bytes from L2 into LDS, which is what limits these kernels, and the CUs they leave free
@@ -892,9 +998,8 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int o
     long t256 = 0;
     for (int i = 0; i < count; ++i) t256 += (long)((g[i].m + 255) / 256) * ((g[i].n + 255) / 256);
     const TileChoice forced = forced_tile();
-    const int tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= 160 ? 256 : 128);
-    hipStream_t s = (hipStream_t)stream;
-    if (tile != 256 || forced.bm) return launch_group_tiled(count, g, bsum, overwrite, tile, s);
+    plan->tile = forced.bm == 256 || forced.bm == 128 ? forced.bm : (t256 >= 160 ? 256 : 128);
+    if (plan->tile != 256 || forced.bm) return CHIMERA_OK;
     // a nearly empty last round: the last row bands of one product go to a 128x128 launch
     int best_p = -1, best_b = 0;
     double best_rounds = 1e30;
@@ -905,18 +1010,34 @@ int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int o
         const double est = (double)((t256 - (long)b * tn + NUM_CUS - 1) / NUM_CUS) + 0.45 * (double)(((long)b * 2 * ((g[p].n + 127) / 128) + NUM_CUS - 1) / NUM_CUS);
         if (est < best_rounds) { best_rounds = est; best_p = p; best_b = b; }
     }
-    if (best_p < 0) return launch_group_tiled(count, g, bsum, overwrite, 256, s);
-    GemmArgs head[GROUP_MAX];
-    for (int i = 0; i < count; ++i) head[i] = g[i];
+    if (best_p < 0) return CHIMERA_OK;
     const size_t m0 = (size_t)((g[best_p].m + 255) / 256 - best_b) * 256;
-    head[best_p].m = (int)m0;
-    GemmArgs tail = g[best_p];
-    tail.m = g[best_p].m - (int)m0;
-    tail.a = (const char*)tail.a + m0 * 2;                      // A is [k, m]: the band starts m0 columns in
-    tail.c = (char*)tail.c + m0 * tail.n * sizeof(float);
-    if (int rc = launch_group_tiled(count, head, bsum, overwrite, 256, s)) return rc;
-    return launch_group_tiled(1, &tail, nullptr, overwrite, 128, s);   // the column sums come from the first launch
+    plan->head[best_p].m = (int)m0;
+    plan->tail = g[best_p];
+    plan->tail.m = g[best_p].m - (int)m0;
+    plan->tail.a = (const char*)plan->tail.a + m0 * 2;                      // A is [k, m]: the band starts m0 columns in
+    plan->tail.c = (char*)plan->tail.c + m0 * plan->tail.n * sizeof(float);
+    plan->has_tail = 1; plan->tail_of = best_p;
+    return CHIMERA_OK;
 }
+
+int gemm_mfma_group_launch_head(const GemmGroupPlan& plan, float* const* bsum, int overwrite, void* stream) {
+    return launch_group_tiled(plan.count, plan.head, bsum, overwrite, plan.tile, (hipStream_t)stream);
+}
+
+int gemm_mfma_group_launch_tail(const GemmGroupPlan& plan, int overwrite, void* stream) {
+    if (!plan.has_tail) return CHIMERA_OK;
+    return launch_group_tiled(1, &plan.tail, nullptr, overwrite, 128, (hipStream_t)stream, false);   // the column sums come from the head
+}
+
+int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream) {
+    GemmGroupPlan plan;
+    if (int rc = gemm_mfma_group_plan(count, g, &plan)) return rc;
+    if (int rc = gemm_mfma_group_launch_head(plan, bsum, overwrite, stream)) return rc;
+    return gemm_mfma_group_launch_tail(plan, overwrite, stream);
+}
+
+const char* gemm_mfma_last_group_kernel() { return g_last_group_kernel; }
 
 int gemm_mfma_set_tuning(int bm, int bn, int splits, int async_mode) {
     if (!((bm == 0 && bn == 0) || (bm == 128 && bn == 128) || (bm == 256 && bn == 256)))

@@ -73,7 +73,15 @@ bool gemm_mfma_supports(const GemmArgs& g);
 // overwrite != 0: C_p and bsum_p receive the results instead of accumulating them
 bool gemm_mfma_group_supports(int count, const GemmArgs* g);
 int gemm_mfma_bf16_group(int count, const GemmArgs* g, float* const* bsum, int overwrite, void* stream);
+// The same in steps, for callers that time the kernels one by one: the plan says which tile the
+// group takes and whether the last row bands of one product (`tail`, product `tail_of`) leave as a
+// second launch of 128x128 tiles; `head` holds the products of the first launch.
+struct GemmGroupPlan { GemmArgs head[4]; GemmArgs tail; int count, tile, has_tail, tail_of; };
+int gemm_mfma_group_plan(int count, const GemmArgs* g, GemmGroupPlan* plan);
+int gemm_mfma_group_launch_head(const GemmGroupPlan& plan, float* const* bsum, int overwrite, void* stream);
+int gemm_mfma_group_launch_tail(const GemmGroupPlan& plan, int overwrite, void* stream);
 int gemm_mfma_set_tuning(int bm, int bn, int splits, int async_mode);
+const char* gemm_mfma_last_group_kernel();   // instantiation(s) of the last grouped launch on this thread
 size_t gemm_mfma_workspace_bytes(int m, int n, int splits);
 size_t gemm_mfma_workspace_need(int m, int n, int k);   // bytes the tile heuristic wants for this shape (0 = none)
 

@@ -28,7 +28,7 @@ static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a
 
 // Optional per-kernel-class timing: a HIP event pair around every launch of a
 // class on the stage's stream, summed after the stream has been waited for.
-enum ProfClass { PC_GEMM_FWD, PC_GEMM_DGRAD, PC_GEMM_WGRAD, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD, PC_LN_BWD, PC_COLSUM, PC_COUNT };
+enum ProfClass { PC_GEMM_FWD, PC_GEMM_DGRAD, PC_GEMM_WGRAD, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD, PC_LN_BWD, PC_COLSUM, PC_GEMM_WGRAD_TAIL, PC_COUNT };
 struct ProfRec { hipEvent_t a, b; int cls; double work; };
 struct Profiler {
     bool on = false;
@@ -172,6 +172,8 @@ void layout(chimera_stage* st) {
     st->ws_bytes = b;
 }
 
+#define TRY(expr) do { int rc__ = (expr); if (rc__) return rc__; } while (0)
+
 int gemm(chimera_stage* st, const GemmArgs& g, int cls, hipStream_t stream) {
     ProfScope prof(cls, 2.0 * g.m * g.n * g.k, stream);
     if (st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_supports(g)) return gemm_mfma_bf16(g, stream);
@@ -214,11 +216,20 @@ int linear_wgrad(chimera_stage* st, int m, int n, int k, const void* x, const vo
 bool wgrad_group_ok(const chimera_stage* st, const GemmArgs (&g)[4]) {
     return st->dtype == CHIMERA_BF16 && st->kernels == 0 && gemm_mfma_group_supports(4, g);
 }
+// One or two launches (the second takes the last row bands of one product on smaller tiles),
+// each timed as a class of its own so that a class is one kernel.
 int wgrad_group(chimera_stage* st, const GemmArgs (&g)[4], float* const (&db)[4], int overwrite, hipStream_t stream) {
+    GemmGroupPlan plan;
+    TRY(gemm_mfma_group_plan(4, g, &plan));
     double flop = 0;
-    for (const GemmArgs& a : g) flop += 2.0 * a.m * a.n * a.k;
-    ProfScope prof(PC_GEMM_WGRAD, flop, stream);
-    return gemm_mfma_bf16_group(4, g, db, overwrite, stream);
+    for (int i = 0; i < plan.count; ++i) flop += 2.0 * plan.head[i].m * plan.head[i].n * plan.head[i].k;
+    {
+        ProfScope prof(PC_GEMM_WGRAD, flop, stream);
+        TRY(gemm_mfma_group_launch_head(plan, db, overwrite, stream));
+    }
+    if (!plan.has_tail) return CHIMERA_OK;
+    ProfScope prof(PC_GEMM_WGRAD_TAIL, 2.0 * plan.tail.m * plan.tail.n * plan.tail.k, stream);
+    return gemm_mfma_group_launch_tail(plan, overwrite, stream);
 }
 
 // Performs a zeroing that chimera_stage_zero_grads deferred.
@@ -233,7 +244,6 @@ int attn_args(chimera_stage* st, AttnArgs& a) {
     return 0;
 }
 
-#define TRY(expr) do { int rc__ = (expr); if (rc__) return rc__; } while (0)
 
 // useful attention flop: 4 S^2 d per (sequence, head) forward (x 1/2 causal, exactly (S+1)/(2S)), 2x that backward
 double attn_flop(const chimera_stage* st) {
@@ -828,6 +838,8 @@ int chimera_op_gemm(int dtype, int impl, int epilogue, int gelu_kind, int m, int
 }
 
 size_t chimera_op_gemm_workspace_bytes(int m, int n, int k) { return gemm_mfma_workspace_need(m, n, k); }
+
+const char* chimera_op_gemm_group_last_kernel(void) { return gemm_mfma_last_group_kernel(); }
 
 int chimera_op_gemm_tuning(int tile_m, int tile_n, int splits, int async_mode) {
     return gemm_mfma_set_tuning(tile_m, tile_n, splits, async_mode);
