@@ -197,16 +197,20 @@ def main():
     }
 
     if not args.no_profile:
-        # one more iteration, same launches, with a HIP event pair around every kernel launch class
-        b.chimera_profile_reset()
-        b.chimera_profile_enable(True)
+        # two more iterations, same launches: one with an event pair around every op (F_t, B_t), one
+        # with an event pair around every kernel launch (the per-kernel events cost some 20 % of an
+        # op's time, so the two are not taken together)
         b.chimera_worker_set_timing(True)
         step()
         torch.cuda.synchronize()
-        b.chimera_profile_enable(False)
         b.chimera_worker_set_timing(False)
-        prof = b.chimera_profile_read()
         tm = b.chimera_worker_last_timing()
+        b.chimera_profile_reset()
+        b.chimera_profile_enable(True)
+        step()
+        torch.cuda.synchronize()
+        b.chimera_profile_enable(False)
+        prof = b.chimera_profile_read()
         # dominant kernel by total time (rocprofv3 kernel trace): the weight-gradient GEMM instance
         wg = prof["gemm_wgrad"]
         achieved = wg["work"] / (wg["ms"] * 1e-3) / 1e12 if wg["ms"] else 0.0
