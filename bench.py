@@ -61,6 +61,24 @@ def _cpu_baseline(cfg):
     }
 
 
+def _single_stream(args):
+    """This benchmark again in a child process with --no-overlap: iteration time and per-kernel-class
+    fractions when no two kernels share the chip."""
+    import subprocess
+    cmd = [sys.executable, os.path.abspath(__file__), "--no-overlap", "--no-cpu-baseline", "--config", args.config,
+           "--rank", str(args.rank), "--steps", str(max(3, args.steps // 2)), "--warmup", "2", "--schedule", args.schedule,
+           "--micro-batches", str(args.micro_batches), "--f", str(args.f)]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    if r.returncode:
+        return {"error": (r.stderr or r.stdout)[-300:]}
+    d = json.loads(r.stdout.strip().splitlines()[-1])
+    return {"value": d["value"], "ms_per_step": d["ms_per_step"],
+            "roofline_kernel_frac": d["roofline"]["frac"], "roofline_kernel_avg_launch_us": d["roofline"]["avg_launch_us"],
+            "all_stage_gemms_frac_mfma_peak": d["all_stage_gemms"]["frac_mfma_peak"],
+            "kernel_classes": {k: v.get("frac_mfma_peak", v.get("frac_hbm_peak")) for k, v in d["kernel_classes"].items()},
+            "note": "bench.py --no-overlap: weight gradients on the stage's own stream, every kernel alone on the chip"}
+
+
 def _time_edges(cfg, dtype, vocab):
     """The pipeline's two ends on one micro-batch of the workload (section 4.1): embedding
     forward + backward, and final LayerNorm + vocabulary projection + cross-entropy, forward
@@ -112,6 +130,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="single stream per stage (analysis only)")
+    ap.add_argument("--no-single-stream", action="store_true", help="skip the extra --no-overlap pass that gives context fractions")
     ap.add_argument("--schedule", choices=["direct", "doubling", "halving"], default="direct",
                     help="direct concatenation (the headline workload), forward doubling with recomputation, or backward halving")
     ap.add_argument("--micro-batches", type=int, default=0, help="N (default: the workload's; doubling needs >= 2D)")
@@ -303,6 +322,10 @@ def main():
         del src, dst
     if args.edges:
         out["edges"] = _time_edges(cfg, dtype, args.vocab)
+    if not args.no_profile and not args.no_overlap and not args.no_single_stream:
+        # The same workload with every kernel alone on the chip (one stream per stage): context for the
+        # fractions above, whose durations include sharing the chip with the stage's second stream.
+        out["single_stream"] = _single_stream(args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(cfg)
     print(json.dumps(out))

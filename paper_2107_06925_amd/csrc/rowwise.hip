@@ -398,32 +398,41 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 // The same for `gridDim.y` partial blocks at once (the LayerNorm backward passes of a whole
 // stage): block row y reduces partial + y * part_stride, laid out [nparts][dgamma | dbeta], into
 // the gradients of LayerNorm y = 2 * layer + (0: first, 1: second LayerNorm of the block).
+// A block of 256 threads owns 64 columns: thread (q, c) sums parts q, q+16, q+32, ... of the four
+// columns 4c..4c+3 (16-byte loads, four in flight), then the 16 sub-sums meet in LDS in fixed order.
 __global__ __launch_bounds__(256) void reduce_partials_batched_kernel(const float* __restrict__ partial, size_t part_stride,
                                                                       int nparts, int cols, float* __restrict__ grads,
                                                                       size_t layer_stride, LnGradOffsets off, int overwrite) {
-    __shared__ float red[8][32];
-    const int c = threadIdx.x & 31, q = threadIdx.x >> 5, n = 2 * cols;
-    const int i = blockIdx.x * 32 + c, y = blockIdx.y;
+    __shared__ float4 red[16][16];
+    const int c = threadIdx.x & 15, q = threadIdx.x >> 4, n = 2 * cols;
+    const int i = blockIdx.x * 64 + c * 4, y = blockIdx.y;
     const float* part = partial + (size_t)y * part_stride;
-    float s = 0.f;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto add = [&](const float4& v) { s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w; };
     if (i < n) {
         int p = q;
-        for (; p + 24 < nparts; p += 32) {
-            const float a0 = part[(size_t)p * n + i], a1 = part[(size_t)(p + 8) * n + i];
-            const float a2 = part[(size_t)(p + 16) * n + i], a3 = part[(size_t)(p + 24) * n + i];
-            s += (a0 + a1) + (a2 + a3);
+        for (; p + 48 < nparts; p += 64) {
+            const float4 a0 = *reinterpret_cast<const float4*>(part + (size_t)p * n + i);
+            const float4 a1 = *reinterpret_cast<const float4*>(part + (size_t)(p + 16) * n + i);
+            const float4 a2 = *reinterpret_cast<const float4*>(part + (size_t)(p + 32) * n + i);
+            const float4 a3 = *reinterpret_cast<const float4*>(part + (size_t)(p + 48) * n + i);
+            add(make_float4((a0.x + a1.x) + (a2.x + a3.x), (a0.y + a1.y) + (a2.y + a3.y), (a0.z + a1.z) + (a2.z + a3.z),
+                            (a0.w + a1.w) + (a2.w + a3.w)));
         }
-        for (; p < nparts; p += 8) s += part[(size_t)p * n + i];
+        for (; p < nparts; p += 16) add(*reinterpret_cast<const float4*>(part + (size_t)p * n + i));
     }
     red[q][c] = s;
     __syncthreads();
     if (q == 0 && i < n) {
-        float t = red[0][c];
+        float4 t = red[0][c];
 #pragma unroll
-        for (int k = 1; k < 8; ++k) t += red[k][c];
+        for (int k = 1; k < 16; ++k) { const float4 v = red[k][c]; t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w; }
         float* g = grads + (size_t)(y >> 1) * layer_stride;
+        // cols is a multiple of 8, so the four columns lie on one side of the dgamma | dbeta seam
         float* dst = i < cols ? g + off.gamma[y & 1] + i : g + off.beta[y & 1] + (i - cols);
-        *dst = overwrite ? t : *dst + t;
+        const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[e] = overwrite ? tv[e] : dst[e] + tv[e];
     }
 }
 
@@ -581,7 +590,7 @@ int layernorm_bwd_reduce(int dtype, int rows, int cols, int count, const float* 
     if (count < 1) return CHIMERA_OK;
     if (rows < 1 || cols < 1 || !partial || !grads || count > 65535) return fail(CHIMERA_EINVAL, "layernorm backward reduce: bad arguments");
     const int nblk = dtype == CHIMERA_F32 ? ln_bwd_blocks<float>(rows, cols) : ln_bwd_blocks<bf16_t>(rows, cols);
-    hipLaunchKernelGGL(reduce_partials_batched_kernel, dim3((2 * cols + 31) / 32, count), dim3(256), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(reduce_partials_batched_kernel, dim3((2 * cols + 63) / 64, count), dim3(256), 0, (hipStream_t)stream,
                        partial, part_stride, nblk, cols, grads, layer_stride, off, overwrite);
     CHIMERA_LAUNCH_CHECK("layernorm backward reduce (batched)");
     return CHIMERA_OK;
