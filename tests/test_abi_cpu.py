@@ -339,3 +339,26 @@ def test_fewer_micro_batches_than_stages_bit_exact(D, N):
         assert got["stash_peak"] == ref["stash_peak"] and got["critical"] == ref["critical"]
     with pytest.raises(b.ChimeraError):
         b.chimera_schedule_pipes(b.DIRECT, 8, 2, 2, 0)          # N < D only with two pipelines
+
+
+def test_schedule_binding_holds_a_halving_list():
+    """A backward-halving list has three ops per micro-batch; the two-argument schedule call must hold it."""
+    ops = b.chimera_schedule(b.HALVING, 4, 8, 0)
+    assert len(ops) == 24
+    assert [o.astuple() for o in ops] == [o.astuple() for o in b.chimera_schedule_pipes(b.HALVING, 4, 8, 1, 0)]
+
+
+@pytest.mark.parametrize("args", [(64, 64, 0, 0), (256, 128, 0, 0), (256, 256, 9, 0), (256, 256, -1, 0), (0, 0, 0, 4), (0, 0, 0, -1)])
+def test_gemm_tuning_rejects_unknown_values(args):
+    """The tuning call is host-only state: anything but 0x0 / 128x128 / 256x256, 0..8 splits and modes 0..3 is EINVAL."""
+    assert b.lib().chimera_op_gemm_tuning(*args) == b.EINVAL
+    assert b.last_error()
+    assert b.lib().chimera_op_gemm_tuning(0, 0, 0, 0) == b.OK
+
+
+def test_no_alloc_limit_and_group_kernel_name_without_a_gpu():
+    lim = b.lib().chimera_op_layernorm_bwd_noalloc_max_scratch_floats()
+    assert lim == 4 << 20
+    # the scratch a shape needs is what the ordinary entry point asks its caller for
+    assert b.lib().chimera_op_layernorm_bwd_scratch_floats(4096, 2048) <= lim < b.lib().chimera_op_layernorm_bwd_scratch_floats(8192, 2048)
+    assert b.lib().chimera_op_gemm_group_last_kernel() == b""      # nothing launched in this process
