@@ -3,13 +3,15 @@
 //
 //   forward   per (sequence, head, 128 queries): loop over 64-key tiles with an
 //             online softmax; writes ctx and the log-sum-exp of every row.
-//   backward  two kernels that both rebuild P = exp(q k^T / sqrt(d) - lse) from
+//   backward  two roles that both rebuild P = exp(q k^T / sqrt(d) - lse) from
 //             the saved log-sum-exp:
-//             dQ    per (sequence, head, 128 queries) looping over 64-key tiles;
-//                   it also forms delta = rowsum(dctx * ctx) of its queries,
+//             dQ    per (sequence, head, 128 queries) looping over 64-key tiles,
 //             dK/dV per (sequence, head, 128 keys) looping over 64-query tiles.
-//             No atomics: every output element has one owner, so results are
-//             reproducible bit for bit.
+//             With many (sequence, head) pairs they are two launches and the dQ
+//             one forms delta = rowsum(dctx * ctx) of its queries on the way;
+//             with few pairs a small kernel forms delta first and both roles
+//             share one launch.  No atomics: every output element has one
+//             owner, so results are reproducible bit for bit.
 //
 // Register/LDS choreography.  v_mfma_f32_32x32x16_bf16 takes, per lane l, 8
 // contraction values of row (or column) l%32; which 8 contraction indices a
@@ -107,8 +109,8 @@ __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, WAVE)
 // works through its tiles before the next group starts.  With the causal mask a tile's work grows
 // with its position, so the longest tiles of ALL pairs are dispatched first (rank slowest).
 template <bool CAUSAL>
-__device__ __forceinline__ bool attn_tile_of(int S, int heads, int batch, int& rank, int& h, int& b) {
-    const int T = (S + 127) / 128, bid = (int)blockIdx.x;
+__device__ __forceinline__ bool attn_tile_of(int bid, int S, int heads, int batch, int& rank, int& h, int& b) {
+    const int T = (S + 127) / 128;
     const int pairs = heads * batch, padded = (pairs + 7) & ~7;
     int p;
     if constexpr (CAUSAL) {
@@ -139,9 +141,9 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
     constexpr int KS = D / 16, OT = D / 32;
     __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * D];
     __shared__ __attribute__((aligned(16))) bf16_t Vs[2][64 * D];
-    const int H = heads * D, ld = 3 * H;
+    const int H = heads * D, ld = 3 * H, bid = (int)blockIdx.x;
     int rank, h, b;
-    if (!attn_tile_of<CAUSAL>(S, heads, batch, rank, h, b)) return;
+    if (!attn_tile_of<CAUSAL>(bid, S, heads, batch, rank, h, b)) return;
     const int q0 = ((S + 127) / 128 - 1 - rank) * 128;       // longest (causal) tiles first
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* Kg = base + H;
@@ -270,18 +272,27 @@ __global__ __launch_bounds__(NT) void attn_fwd_kernel(const bf16_t* __restrict__
 // work on the current one; each 32-query half of a tile is finished (scores to dK/dV) before
 // the next starts, which keeps the live score registers at 32.  Rows beyond the sequence
 // repeat its last row; their P is masked to zero.
+// LDS of one backward workgroup: two tensors x two stages of [64][D] tiles, and (dK/dV role) the
+// statistics of a tile's 64 queries.
+template <int D> struct AttnBwdLds {
+    bf16_t t0[2][64 * D], t1[2][64 * D];
+    float lse2[2][64], dl[2][64];
+};
+
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                          bf16_t* __restrict__ dqkv, int S, int heads, int batch,
-                                                          float scale) {
+__device__ __forceinline__ void attn_bwd_dkv_role(AttnBwdLds<D>& sm, int bid, const bf16_t* __restrict__ qkv,
+                                                  const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
+                                                  const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S,
+                                                  int heads, int batch, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
     constexpr unsigned TILE_BYTES = 64 * D * 2;
-    __shared__ __attribute__((aligned(16))) bf16_t Qs[2][64 * D], Os[2][64 * D];
-    __shared__ __attribute__((aligned(16))) float lse2[2][64], dl[2][64];
+    bf16_t (&Qs)[2][64 * D] = sm.t0;
+    bf16_t (&Os)[2][64 * D] = sm.t1;
+    float (&lse2)[2][64] = sm.lse2;
+    float (&dl)[2][64] = sm.dl;
     const int H = heads * D, ld = 3 * H;
     int rank, h, b;
-    if (!attn_tile_of<CAUSAL>(S, heads, batch, rank, h, b)) return;
+    if (!attn_tile_of<CAUSAL>(bid, S, heads, batch, rank, h, b)) return;
     const int j0 = rank * 128;             // the first keys meet the most queries
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* dOg = dctx + (size_t)b * S * H + h * D;
@@ -399,17 +410,21 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restri
 // dQ of 128 queries (32 per wavefront), looping over 64-key tiles.
 //   S^T = K Q^T (keys x queries)   P = exp2(S^T c - lse2)   dP^T = V dO^T
 //   dS^T = P (dP^T - delta)        dQ^T += K^T dS^T (then * 1/sqrt(d))
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                         const bf16_t* __restrict__ ctx, const float* __restrict__ lse,
-                                                         float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S,
-                                                         int heads, int batch, float scale) {
+// FORM_DELTA: delta = rowsum(dO * O) of the workgroup's queries is formed here (from the dO
+// fragments the wavefront holds anyway and the same pieces of O) and written out for the dK/dV
+// kernel that follows; otherwise it is read (attn_delta_kernel has run).
+template <int D, bool CAUSAL, bool FORM_DELTA>
+__device__ __forceinline__ void attn_bwd_dq_role(AttnBwdLds<D>& sm, int bid, const bf16_t* __restrict__ qkv,
+                                                 const bf16_t* __restrict__ dctx, const bf16_t* __restrict__ ctx,
+                                                 const float* __restrict__ lse, float* __restrict__ delta,
+                                                 bf16_t* __restrict__ dqkv, int S, int heads, int batch, float scale) {
     constexpr int KS = D / 16, OT = D / 32;
     constexpr unsigned TILE_BYTES = 64 * D * 2;
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[2][64 * D], Vs[2][64 * D];
+    bf16_t (&Ks)[2][64 * D] = sm.t0;
+    bf16_t (&Vs)[2][64 * D] = sm.t1;
     const int H = heads * D, ld = 3 * H;
     int rank, h, b;
-    if (!attn_tile_of<CAUSAL>(S, heads, batch, rank, h, b)) return;
+    if (!attn_tile_of<CAUSAL>(bid, S, heads, batch, rank, h, b)) return;
     const int q0 = ((S + 127) / 128 - 1 - rank) * 128;
     const bf16_t* base = qkv + (size_t)b * S * ld + h * D;
     const bf16_t* dOg = dctx + (size_t)b * S * H + h * D;
@@ -435,10 +450,9 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restric
         of[kk] = load_frag(dOg + (size_t)qrow * H + kk * 16 + g * 8, qrow < S);
     }
     const float my_lse2 = qrow < S ? lse[stat0 + qrow] * LOG2E : 0.f;
-    // delta = rowsum(dO * O) of this lane's query: the lane pair (l, l^32) holds the whole row
-    // of dO; the same pieces of O are fetched once.  Written out for the dK/dV kernel.
     float my_dl = 0.f;
-    {
+    if constexpr (FORM_DELTA) {
+        // the lane pair (l, l^32) holds the whole row of dO
         const bf16_t* Og = ctx + (size_t)b * S * H + h * D;
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
@@ -448,6 +462,8 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restric
         }
         my_dl += xor32(my_dl);
         if (g == 0 && qrow < S) delta[stat0 + qrow] = my_dl;
+    } else {
+        my_dl = qrow < S ? delta[stat0 + qrow] : 0.f;
     }
     f32x16 dq[OT];
 #pragma unroll
@@ -515,6 +531,67 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restric
     }
 }
 
+// delta[sequence, head, position] = sum over the head dimension of dO * O: one lane per 8 elements
+// (16 bytes of each tensor), the D / 8 lanes of a (token, head) pair side by side.
+template <int D>
+__global__ __launch_bounds__(NT) void attn_delta_kernel(const bf16_t* __restrict__ dctx, const bf16_t* __restrict__ ctx,
+                                                        float* __restrict__ delta, int S, int heads, int batch) {
+    constexpr int LPH = D / 8;                                   // lanes per (token, head)
+    const size_t H = (size_t)heads * D, chunks = (size_t)batch * S * heads * LPH;
+    const size_t c = (size_t)blockIdx.x * NT + threadIdx.x;
+    float v = 0.f;
+    if (c < chunks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(dctx + c * 8);
+        const bf16x8 o = *reinterpret_cast<const bf16x8*>(ctx + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v += (float)a[e] * (float)o[e];
+    }
+#pragma unroll
+    for (int off = LPH / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    if (c < chunks && (c % LPH) == 0) {
+        const size_t th = c / LPH, token = th / heads, h = th % heads;      // token = sequence * S + position
+        delta[((token / S) * heads + h) * S + token % S] = v;
+    }
+    (void)H;
+}
+
+// Both backward kernels in one launch: workgroups come in groups of 8 (one per XCD), the groups
+// alternate between the dK/dV role and the dQ role, and a workgroup's number within its role keeps
+// its id mod 8, so that a (sequence, head) pair's tiles of both roles meet in one L2.  The two
+// roles are independent (delta comes from attn_delta_kernel), so with few pairs - where one role
+// alone leaves the chip half empty and its longest causal tile sets the time - each fills the
+// other's gaps.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(NT) void attn_bwd_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                      const float* __restrict__ lse, const float* __restrict__ delta,
+                                                      bf16_t* __restrict__ dqkv, int S, int heads, int batch, float scale) {
+    __shared__ __attribute__((aligned(16))) AttnBwdLds<D> sm;
+    const int blk = (int)blockIdx.x;
+    const int role = (blk >> 3) & 1, bid = ((blk >> 4) << 3) | (blk & 7);
+    if (role == 0) attn_bwd_dkv_role<D, CAUSAL>(sm, bid, qkv, dctx, lse, delta, dqkv, S, heads, batch, scale);
+    else attn_bwd_dq_role<D, CAUSAL, false>(sm, bid, qkv, dctx, nullptr, lse, const_cast<float*>(delta), dqkv, S, heads, batch, scale);
+}
+
+// The roles as launches of their own, dQ first (it forms delta): for many pairs, where each role
+// fills the chip by itself and the merged kernel's register count (that of its larger role) would
+// only cost the other role wavefronts per SIMD.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(NT) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                         const bf16_t* __restrict__ ctx, const float* __restrict__ lse,
+                                                         float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S,
+                                                         int heads, int batch, float scale) {
+    __shared__ __attribute__((aligned(16))) AttnBwdLds<D> sm;
+    attn_bwd_dq_role<D, CAUSAL, true>(sm, (int)blockIdx.x, qkv, dctx, ctx, lse, delta, dqkv, S, heads, batch, scale);
+}
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(NT) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                          const float* __restrict__ lse, const float* __restrict__ delta,
+                                                          bf16_t* __restrict__ dqkv, int S, int heads, int batch,
+                                                          float scale) {
+    __shared__ __attribute__((aligned(16))) AttnBwdLds<D> sm;
+    attn_bwd_dkv_role<D, CAUSAL>(sm, (int)blockIdx.x, qkv, dctx, lse, delta, dqkv, S, heads, batch, scale);
+}
+
 int check(const AttnArgs& a) {
     if (!attention_mfma_supports(a)) return fail(CHIMERA_EINVAL, "matrix-core attention: unsupported shape (head_dim %d)", a.head_dim);
     return CHIMERA_OK;
@@ -551,14 +628,26 @@ int attention_bwd_mfma(const AttnArgs& a, void* stream) {
     if (((uintptr_t)a.ctx | (uintptr_t)a.dctx | (uintptr_t)a.dqkv) & 15) return fail(CHIMERA_EINVAL, "attention buffers must be 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const dim3 block(NT);
-    const dim3 grid(attn_grid(a));
+    const dim3 grid(attn_grid(a)), grid2(2 * attn_grid(a));    // one role / both roles; attn_grid is a multiple of 8
+    const size_t chunks = (size_t)a.batch * a.seq * a.heads * (a.head_dim / 8);
+    const dim3 dgrid((unsigned)((chunks + NT - 1) / NT));
     const float scale = 1.0f / sqrtf((float)a.head_dim);
+    // Few (sequence, head) pairs: one launch with both roles (measured: 448 workgroups per role
+    // 58 -> 53 us, 256 per role at head dim 128 149 -> 119 us; 512 and more per role are faster apart).
+    const bool merged = attn_grid(a) <= 480;
 #define ATTN_BWD(D, C)                                                                                              \
     do {                                                                                                            \
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx,  \
-                           (const bf16_t*)a.ctx, a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, a.batch, scale);   \
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx, \
-                           a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, a.batch, scale);                        \
+        if (merged) {                                                                                               \
+            hipLaunchKernelGGL((attn_delta_kernel<D>), dgrid, block, 0, s, (const bf16_t*)a.dctx, (const bf16_t*)a.ctx, \
+                               a.delta, a.seq, a.heads, a.batch);                                                   \
+            hipLaunchKernelGGL((attn_bwd_kernel<D, C>), grid2, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx, \
+                               a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, a.batch, scale);                     \
+        } else {                                                                                                    \
+            hipLaunchKernelGGL((attn_bwd_dq_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx, \
+                               (const bf16_t*)a.ctx, a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, a.batch, scale); \
+            hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, C>), grid, block, 0, s, (const bf16_t*)a.qkv, (const bf16_t*)a.dctx, \
+                               a.lse, a.delta, (bf16_t*)a.dqkv, a.seq, a.heads, a.batch, scale);                    \
+        }                                                                                                           \
     } while (0)
     if (a.head_dim == 64) { if (a.causal) ATTN_BWD(64, true); else ATTN_BWD(64, false); }
     else { if (a.causal) ATTN_BWD(128, true); else ATTN_BWD(128, false); }
