@@ -905,11 +905,13 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
     if (t.splits > 1 && (size_t)((g.m + 255) / 256) * ((g.n + 255) / 256) * sizeof(unsigned) > SPLITK_COUNTER_BYTES)
         return fail(CHIMERA_EINVAL, "too many tiles for split-K");
     // the async kernels cannot zero-fill: whole k steps only, and at least 8 rows on each side.
-    // 128x128 tiles: with fewer than two workgroups per CU, a workgroup of 4 wavefronts leaves
-    // one wavefront per SIMD, and nothing covers its LDS latency and the barrier of every k
-    // step; then 8 wavefronts share the tile, two per 64x64 block, each taking half of every
-    // k step (their partial sums meet in LDS at the end), over a 4-stage ring.  With two or
-    // more workgroups per CU the 2-stage ring (64 KiB of LDS, so two workgroups fit) is faster.
+    // 128x128 tiles: with one workgroup per CU, a workgroup of 4 wavefronts leaves one wavefront
+    // per SIMD, and nothing covers its LDS latency and the barrier of every k step; then 8
+    // wavefronts share the tile, two per 64x64 block, each taking half of every k step (their
+    // partial sums meet in LDS at the end), over a 3-stage ring of 96 KiB - one such workgroup
+    // per CU, so more than NUM_CUS tiles would take it two rounds.  Beyond that the 4-wavefront
+    // form with its 2-stage ring (64 KiB of LDS, two workgroups per CU) is faster: 416 tiles of a
+    // 4096 x 1600 x 6400 product take 109 us against 124 us, 208 tiles (2048 rows) 89 against 62.
     const int mode = tuning().async_mode;
     const bool can_async = g.k % BK == 0 && g.m >= 8 && g.n >= 8 && t.splits == 1 && mode != ASYNC_OFF;
     if (can_async) {
@@ -929,14 +931,14 @@ int gemm_mfma_bf16(const GemmArgs& g, void* stream) {
                 if (g.r) tail.r = (const char*)g.r + m0 * g.n * (g.r_f32 ? 4 : 2);
                 if (int rc = launch_async<256, 256, 2, 4, 1, 2>(head, s)) return rc;
                 const long t128 = (long)((tail.m + 127) / 128) * ((tail.n + 127) / 128);
-                if (t128 < 2 * NUM_CUS) return launch_async<128, 128, 2, 2, 2, 3>(tail, s);
+                if (t128 <= NUM_CUS) return launch_async<128, 128, 2, 2, 2, 3>(tail, s);
                 return launch_async<128, 128, 2, 2, 1, 2>(tail, s);
             }
             return launch_async<256, 256, 2, 4, 1, 2>(g, s);
         }
         if (t.bm == 128 && t.bn == 128) {
             const long t128 = (long)((g.m + 127) / 128) * ((g.n + 127) / 128);
-            const bool ksplit = mode != ASYNC_AUTO ? mode == ASYNC_KSLICED : t128 < 2 * NUM_CUS;
+            const bool ksplit = mode != ASYNC_AUTO ? mode == ASYNC_KSLICED : t128 <= NUM_CUS;
             if (ksplit) return launch_async<128, 128, 2, 2, 2, 3>(g, s);
             return launch_async<128, 128, 2, 2, 1, 2>(g, s);
         }
@@ -975,7 +977,7 @@ int launch_group_tiled(int count, const GemmArgs* g, float* const* bsum, int ove
     if (tile == 256) return launch_group<256, 256, 2, 4, 1, 2>(grp, stream, first);
     // two workgroups per CU or the k-sliced 8-wavefront form
     const int mode = tuning().async_mode;
-    const bool ksplit = mode != ASYNC_AUTO ? mode == ASYNC_KSLICED : tiles < 2 * NUM_CUS;
+    const bool ksplit = mode != ASYNC_AUTO ? mode == ASYNC_KSLICED : tiles <= NUM_CUS;
     if (ksplit) return launch_group<128, 128, 2, 2, 2, 3>(grp, stream, first);
     return launch_group<128, 128, 2, 2, 1, 2>(grp, stream, first);
 }
